@@ -1,0 +1,37 @@
+"""Compile the C oracle with gcc into oracle/libodsgd_oracle.so.
+
+The same source is compiled twice (real=float and real=double) and linked into
+one shared object.  FP contraction is switched off and no -march flag is given,
+so each source line is one IEEE operation (see the header of odsgd_oracle.c).
+"""
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "odsgd_oracle.c")
+LIB = os.path.join(HERE, "libodsgd_oracle.so")
+
+CFLAGS = ["-O2", "-std=c99", "-fPIC", "-ffp-contract=off", "-fno-fast-math",
+          "-fno-unsafe-math-optimizations", "-Wall", "-Wextra", "-Werror"]
+
+
+def build(force=False, extra_cflags=(), lib=LIB, src=SRC):
+    if (not force and os.path.exists(lib)
+            and os.path.getmtime(lib) >= os.path.getmtime(src)):
+        return lib
+    objs = []
+    for real, suffix in (("float", "f32"), ("double", "f64")):
+        obj = lib + "." + suffix + ".o"
+        cmd = ["gcc", *CFLAGS, *extra_cflags, "-DODSGD_REAL=" + real,
+               "-DODSGD_SUFFIX=" + suffix, "-c", src, "-o", obj]
+        subprocess.run(cmd, check=True)
+        objs.append(obj)
+    subprocess.run(["gcc", "-shared", "-o", lib, *objs, *extra_cflags], check=True)
+    for o in objs:
+        os.remove(o)
+    return lib
+
+
+if __name__ == "__main__":
+    print(build(force="--force" in sys.argv))

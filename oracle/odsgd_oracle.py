@@ -1,0 +1,121 @@
+"""ctypes front end of the C oracle (oracle/odsgd_oracle.c).
+
+TEST INFRASTRUCTURE, NOT THE PRODUCT: only tests/, the smoke check and the
+benchmark's cpu_baseline leg may import this module.  It holds no arithmetic of
+its own -- every number comes from the C loops -- and imports nothing from the
+GPU package.
+
+State is a plain dict of numpy arrays, one flat array per parameter tensor:
+    w[k], v[k]          global weights / momentum (updated in place)
+    u[m][k]             worker m's local weights (overwritten)
+    g[m][k]             worker m's gradient (read only)
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_LIB = None
+
+
+def lib():
+    global _LIB
+    if _LIB is None:
+        path = _build.build()
+        _LIB = ctypes.CDLL(path)
+    return _LIB
+
+
+_CT = {np.dtype(np.float32): (ctypes.c_float, "f32"),
+       np.dtype(np.float64): (ctypes.c_double, "f64")}
+
+
+def _ptr_array(arrs, ctype):
+    pp = ctypes.POINTER(ctype)
+    return (pp * len(arrs))(*[a.ctypes.data_as(pp) for a in arrs])
+
+
+def _check(arrs, dtype, n):
+    for a in arrs:
+        assert isinstance(a, np.ndarray) and a.dtype == dtype, (type(a), getattr(a, "dtype", None))
+        assert a.ndim == 1 and a.shape[0] == n and a.flags.c_contiguous
+
+
+def local_update(w, g, u, local_lr, weight_decay, worker=-1):
+    """Worker-side local update, tensor list form. w: [K], g/u: [M][K]."""
+    M = len(g)
+    for k in range(len(w)):
+        dt = w[k].dtype
+        ct, sfx = _CT[dt]
+        n = w[k].shape[0]
+        gk = [g[m][k] for m in range(M)]
+        uk = [u[m][k] for m in range(M)]
+        _check([w[k]] + gk + uk, dt, n)
+        fn = getattr(lib(), "odsgd_oracle_local_" + sfx)
+        fn.restype = None
+        fn(ctypes.c_int64(n), ctypes.c_int(M), w[k].ctypes.data_as(ctypes.POINTER(ct)),
+           _ptr_array(gk, ct), _ptr_array(uk, ct), ctypes.c_int(worker),
+           ct(local_lr), ct(weight_decay))
+
+
+def global_update(w, v, g, lr, momentum, weight_decay, grad_scale=0.0):
+    """Server-side global update, tensor list form. w, v: [K], g: [M][K]."""
+    M = len(g)
+    for k in range(len(w)):
+        dt = w[k].dtype
+        ct, sfx = _CT[dt]
+        n = w[k].shape[0]
+        gk = [g[m][k] for m in range(M)]
+        _check([w[k], v[k]] + gk, dt, n)
+        fn = getattr(lib(), "odsgd_oracle_global_" + sfx)
+        fn.restype = None
+        P = ctypes.POINTER(ct)
+        fn(ctypes.c_int64(n), ctypes.c_int(M), w[k].ctypes.data_as(P), v[k].ctypes.data_as(P),
+           _ptr_array(gk, ct), ct(lr), ct(momentum), ct(weight_decay), ct(grad_scale))
+
+
+def od_step(w, v, g, u, lr, local_lr, momentum, weight_decay, grad_scale=0.0):
+    """One training-stage OD-SGD iteration over a tensor list."""
+    M = len(g)
+    for k in range(len(w)):
+        dt = w[k].dtype
+        ct, sfx = _CT[dt]
+        n = w[k].shape[0]
+        gk = [g[m][k] for m in range(M)]
+        uk = [u[m][k] for m in range(M)]
+        _check([w[k], v[k]] + gk + uk, dt, n)
+        fn = getattr(lib(), "odsgd_oracle_od_step_" + sfx)
+        fn.restype = None
+        P = ctypes.POINTER(ct)
+        fn(ctypes.c_int64(n), ctypes.c_int(M), w[k].ctypes.data_as(P), v[k].ctypes.data_as(P),
+           _ptr_array(gk, ct), _ptr_array(uk, ct), ct(lr), ct(local_lr), ct(momentum),
+           ct(weight_decay), ct(grad_scale))
+
+
+def ssgd_step(w, v, g, u, lr, momentum, weight_decay, grad_scale=0.0):
+    """One warm-up (synchronous SGD) iteration over a tensor list."""
+    M = len(g)
+    for k in range(len(w)):
+        dt = w[k].dtype
+        ct, sfx = _CT[dt]
+        n = w[k].shape[0]
+        gk = [g[m][k] for m in range(M)]
+        uk = [u[m][k] for m in range(M)]
+        _check([w[k], v[k]] + gk + uk, dt, n)
+        fn = getattr(lib(), "odsgd_oracle_ssgd_step_" + sfx)
+        fn.restype = None
+        P = ctypes.POINTER(ct)
+        fn(ctypes.c_int64(n), ctypes.c_int(M), w[k].ctypes.data_as(P), v[k].ctypes.data_as(P),
+           _ptr_array(gk, ct), _ptr_array(uk, ct), ct(lr), ct(momentum),
+           ct(weight_decay), ct(grad_scale))
+
+
+def step(i, warmup_steps, w, v, g, u, lr, local_lr, momentum, weight_decay, grad_scale=0.0):
+    """Iteration i of the whole schedule of Alg. 2: synchronous SGD while
+    i < warmup_steps, one-step-delay iteration from i == warmup_steps on."""
+    if i < warmup_steps:
+        ssgd_step(w, v, g, u, lr, momentum, weight_decay, grad_scale)
+    else:
+        od_step(w, v, g, u, lr, local_lr, momentum, weight_decay, grad_scale)
