@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused OD-SGD step on one MI355X.
+
+A "step" is one pass of the whole update path over the resident state: W-way
+gradient reduce + global momentum-SGD update + W local compensated updates, in
+one launch (odsgd_step).  Inputs (weights, momentum, W gradient buffers) are in
+HBM before the timed region starts.
+
+Prints ONE JSON line:
+  value      params updated per second (N / step time), whole job on the one GPU
+  roofline   algorithmic bytes 8*(W+2)*N per launch / mean kernel duration
+             (HIP events on the launch stream) against the 8 TB/s HBM peak
+  cpu_baseline  the CPU oracle timed on this host on a bounded sample
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs,
+# scaled by the same counters on a plain copy kernel); see profiles/.  None = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+PAPER_CONTEXT = {
+    "note": "the paper reports end-to-end training speed only, never the update path; other hardware, context only",
+    "resnet50_imagenet_90_epochs_4x(4xV100)_IB56": {"SSGD_hours": 10.5, "OD-SGD_hours": 9.2},
+    "resnet18v2_cifar10_4_workers_K80_IB56_samples_per_s": {"SSGD": 236.78, "OD-SGD": 309.782},
+    "mobilenet_mnist_4_workers_K80_10GbE_samples_per_s": {"SSGD": 236.63, "OD-SGD": 401.395},
+}
+
+
+def algorithmic_bytes(n_params, W):
+    return 8 * (W + 2) * n_params
+
+
+def time_gpu(wl_mod, B, torch, name, steps, warmup):
+    w = wl_mod.WORKLOADS[name]
+    dev = "cuda:0"
+    st = wl_mod.allocate(w, dev)
+    wl_mod.fill_all_grads_(st, w, 0)
+    eng = B.Engine(st["w"], st["v"], st["g"], st["u"])
+    hy = B.odsgd_hyper(*w.hyper)
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        eng.step(hy, stream)
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    events[0].record(stream)
+    for i in range(steps):
+        eng.step(hy, stream)
+        events[i + 1].record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    per_launch_ms = [events[i].elapsed_time(events[i + 1]) for i in range(steps)]
+    eng.close()
+    N = wl_mod.total_params(w)
+    return {
+        "workload": name, "tensors": len(w.tensors), "params": N, "workers": w.num_workers,
+        "ms_per_step": (t1 - t0) * 1e3 / steps,
+        "kernel_ms_mean": sum(per_launch_ms) / steps,
+        "kernel_ms_min": min(per_launch_ms),
+        "bytes_per_step": algorithmic_bytes(N, w.num_workers),
+    }, st
+
+
+def summarize(r):
+    out = dict(r)
+    out["params_per_s"] = r["params"] / (r["ms_per_step"] * 1e-3)
+    out["hbm_gbps"] = r["bytes_per_step"] / (r["kernel_ms_mean"] * 1e-3) / 1e9
+    out["hbm_frac"] = out["hbm_gbps"] / HBM_PEAK_GBPS
+    return out
+
+
+def cpu_baseline(wl_mod, name, st, budget_s=12.0):
+    """Time the oracle, as it stands, single-threaded on host copies of the same state."""
+    import numpy as np
+    from oracle import odsgd_oracle as oracle
+    w = wl_mod.WORKLOADS[name]
+    hs = {k: [t.cpu().numpy() for t in st[k]] for k in ("w", "v")}
+    hs["g"] = [[t.cpu().numpy() for t in r] for r in st["g"]]
+    hs["u"] = [[t.cpu().numpy() for t in r] for r in st["u"]]
+    hy = [float(np.float32(x)) for x in w.hyper]
+    N = wl_mod.total_params(w)
+
+    def one():
+        t0 = time.perf_counter()
+        oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], *hy)
+        return time.perf_counter() - t0
+
+    one()  # page in
+    t_first = one()
+    reps = max(1, min(50, int(budget_s / max(t_first, 1e-6))))
+    times = [one() for _ in range(reps)]
+    t = sum(times) / reps
+    return {"value": N / t, "unit": "params/s", "cores": 1, "kind": "oracle",
+            "sample": "%d full OD-SGD steps of the %s parameter set (N=%d, W=%d), single thread, %.2f s each"
+                      % (reps, name, N, w.num_workers, t),
+            "gbps": algorithmic_bytes(N, w.num_workers) / t / 1e9}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="resnet50")
+    ap.add_argument("--others", default="vgg16,alexnet",
+                    help="comma list of further workloads measured in the same run ('' for none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (the W workers are W gradient buffers in "
+                 "one HBM); --gpus %d is not supported, no multi-GPU figure exists" % args.gpus)
+
+    import torch
+    from paper_2005_06728_amd import binding as B
+    from paper_2005_06728_amd import workloads as wl_mod
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    B.lib()  # fail loudly if the extension is missing
+
+    main_r, st = time_gpu(wl_mod, B, torch, args.workload, args.steps, args.warmup)
+    main_s = summarize(main_r)
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(wl_mod, args.workload, st)
+    del st
+    torch.cuda.empty_cache()
+
+    others = {}
+    for name in [x for x in args.others.split(",") if x and x != args.workload]:
+        r, st2 = time_gpu(wl_mod, B, torch, name, max(5, min(args.steps, 20)), args.warmup)
+        del st2
+        torch.cuda.empty_cache()
+        s = summarize(r)
+        others[name] = {k: s[k] for k in ("params", "workers", "ms_per_step", "kernel_ms_mean",
+                                          "params_per_s", "hbm_gbps", "hbm_frac")}
+
+    w = wl_mod.WORKLOADS[args.workload]
+    line = {
+        "metric": "params updated/sec per OD-SGD step (and achieved HBM GB/s, see roofline)",
+        "value": main_s["params_per_s"],
+        "unit": "params/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": main_s["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s-shaped parameter set" % args.workload, "tensors": main_s["tensors"],
+                   "params": main_s["params"], "workers": main_s["workers"],
+                   "hyper": dict(w.hyper._asdict()), "entry_point": "odsgd_step (fused, one launch)"},
+        "roofline": {"bound": "hbm", "achieved": main_s["hbm_gbps"], "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": main_s["hbm_frac"],
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
+                     "algorithmic_bytes_per_launch": main_s["bytes_per_step"],
+                     "kernel_ms_mean": main_s["kernel_ms_mean"], "kernel_ms_min": main_s["kernel_ms_min"]},
+        "cpu_baseline": cpu,
+        "other_workloads": others,
+        "paper_context": PAPER_CONTEXT,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,164 @@
+/*
+ * odsgd.h -- C ABI of the OD-SGD (One-step Delay SGD) parameter-update engine
+ *            for one AMD MI355X (gfx950).
+ *
+ * The engine runs the per-iteration update pipeline that OD-SGD adds to
+ * data-parallel training (paper: Section 3.1, Algorithms 1 and 2; Section 3.3):
+ *
+ *   global update  (Alg. 1, parameter server, taken once all M gradients are in)
+ *       s    = g_0 + g_1 + ... + g_{W-1}          strictly in ascending worker order
+ *       gbar = s * grad_scale
+ *       r    = weight_decay * w_t
+ *       v'   = momentum * v_t - lr * (gbar + r)
+ *       w'   = w_t + v'
+ *   local update   (Alg. 2, worker m, "update w_bak with g_m"; Section 3.3 "Local Updater")
+ *       u_m  = w_t - local_lr * (g_m + r)         w_t = weights BEFORE this
+ *                                                 iteration's global update
+ *   warm-up iteration (Alg. 2, while-loop before the switch: plain synchronous SGD)
+ *       global update, then u_m = w' for every worker
+ *
+ * All tensors are fp32.  Each arithmetic line above is one IEEE-754 binary32
+ * operation, round-to-nearest-even, with no fused multiply-add, so results do
+ * not depend on launch shape.  NaN/Inf inputs propagate; subnormals are kept.
+ *
+ * Memory model.  The caller owns all device memory (weights, momentum,
+ * gradients, local weights and the workspace); the library borrows the
+ * pointers given to odsgd_init until odsgd_destroy and never allocates or
+ * frees device memory.  Every pointer named "device" must be a device address
+ * valid on the GPU that is current when odsgd_init is called.  Arrays named
+ * "host" are read during the call only.
+ *
+ * Execution model.  odsgd_local_update / odsgd_global_update / odsgd_step /
+ * odsgd_ssgd_step enqueue one kernel on the given HIP stream and return
+ * without synchronising.  A handle is not thread-safe; distinct handles are
+ * independent.  On any error no kernel is launched.
+ */
+#ifndef ODSGD_H
+#define ODSGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Error codes (all entry points returning int: 0 on success, negative on error). */
+#define ODSGD_OK 0
+#define ODSGD_EINVAL (-1) /* null pointer, K < 1, W < 1 or > ODSGD_MAX_WORKERS, negative numel, bad worker index */
+#define ODSGD_EALIGN (-2) /* a device pointer is not 4-byte aligned */
+#define ODSGD_EALIAS (-3) /* an output range (w, mom, local_w) overlaps any other registered range */
+#define ODSGD_ENOSPC (-4) /* workspace smaller than odsgd_workspace_bytes() */
+#define ODSGD_EHIP (-5)   /* a HIP runtime call failed */
+#define ODSGD_ERANGE (-6) /* sizes exceed what the tables can index (a tensor >= 2^40 elements, > 2^31-2 chunks) */
+
+#define ODSGD_MAX_WORKERS 64
+
+typedef struct odsgd_handle odsgd_handle; /* opaque; host memory owned by the library */
+
+/*
+ * Hyper-parameters of one call.  The paper names a global and a local learning
+ * rate (Section 4.4: "OD(1.6+0.4)"), momentum for the global updater (Section
+ * 4.2) and weight decay (Section 4.4).  Passed by pointer, read during the call.
+ */
+typedef struct {
+    float lr;           /* global (server) learning rate */
+    float local_lr;     /* local (worker) learning rate */
+    float momentum;     /* global updater only */
+    float weight_decay; /* coupled L2 term, same value in global and local update */
+    float grad_scale;   /* multiplies the W-way gradient sum; <= 0 selects 1.0f/(float)W */
+} odsgd_hyper;
+
+/*
+ * Bytes of device workspace odsgd_init needs for this tensor list (chunk
+ * table + pointer table).  numel: host array of num_tensors element counts.
+ * Returns 0 if the arguments are invalid.
+ */
+size_t odsgd_workspace_bytes(int num_tensors, const int64_t *numel, int num_workers);
+
+/*
+ * Register a parameter set and build the launch plan (Section 2.2 keeps one
+ * <key, value> pair per parameter tensor; here the K tensors become one chunk
+ * table so that a single launch covers all of them).
+ *
+ *   out            receives the handle
+ *   num_tensors    K >= 1
+ *   numel          host, [K]; element count of tensor k (0 is legal and skipped)
+ *   w, mom         host arrays [K] of device pointers: global weights and
+ *                  momentum of tensor k, numel[k] floats each, read and written
+ *   grads          host array [W] of host arrays [K] of device pointers:
+ *                  worker m's gradient of tensor k, read only.  The buffers are
+ *                  registered once; the caller refills them in place each iteration
+ *   local_w        host array [W] of host arrays [K] of device pointers:
+ *                  worker m's local weights of tensor k, written only
+ *   num_workers    1 <= W <= ODSGD_MAX_WORKERS
+ *   workspace      device, >= odsgd_workspace_bytes(...) bytes, 256-byte aligned,
+ *                  must stay valid and untouched until odsgd_destroy
+ *   stream         hipStream_t (as void*) on which the tables are uploaded;
+ *                  the call returns after the upload has completed
+ *
+ * Pointers 16-byte aligned take the 128-bit path; a tensor with any pointer
+ * only 4-byte aligned is processed with 32-bit accesses.  Ranges of w, mom and
+ * local_w must not overlap each other or any gradient (ODSGD_EALIAS);
+ * gradients may alias one another.
+ */
+int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel,
+               float *const *w, float *const *mom,
+               const float *const *const *grads, float *const *const *local_w,
+               int num_workers, void *workspace, size_t workspace_bytes,
+               void *stream);
+
+/*
+ * Local update (Alg. 2, training stage): local_w[m] = w - local_lr*(grads[m] + wd*w)
+ * for worker m = `worker`, or for all workers if worker == -1.  Reads w as it is
+ * when the kernel runs: for iteration t it must be enqueued BEFORE that
+ * iteration's odsgd_global_update.  Uses hyper->local_lr and hyper->weight_decay.
+ */
+int odsgd_local_update(odsgd_handle *h, int worker, const odsgd_hyper *hyper, void *stream);
+
+/*
+ * Global update (Alg. 1): W-way gradient reduce and momentum-SGD step on w and
+ * mom, in place.  Uses lr, momentum, weight_decay, grad_scale.  Advances the
+ * handle's iteration counter by one.
+ */
+int odsgd_global_update(odsgd_handle *h, const odsgd_hyper *hyper, void *stream);
+
+/*
+ * One iteration of the whole schedule of Alg. 2 in a single launch.  With i the
+ * handle's iteration counter and wp the warm-up length (odsgd_set_warmup,
+ * default 0):
+ *   i >= wp : one-step-delay iteration -- bitwise identical to
+ *             odsgd_local_update(h, -1, ...) followed by odsgd_global_update(h, ...)
+ *   i <  wp : warm-up iteration        -- identical to odsgd_ssgd_step
+ * Reads w, mom and the W gradients once and writes w, mom and the W local
+ * weights once.  Advances the iteration counter by one.
+ */
+int odsgd_step(odsgd_handle *h, const odsgd_hyper *hyper, void *stream);
+
+/*
+ * Warm-up iteration regardless of the counter: global update, then every
+ * local_w[m] receives the new global weights.  Advances the iteration counter.
+ */
+int odsgd_ssgd_step(odsgd_handle *h, const odsgd_hyper *hyper, void *stream);
+
+/*
+ * Warm-up length wp >= 0 (Alg. 2 input): iterations 0..wp-1 are synchronous SGD,
+ * the first local update happens in iteration wp.
+ */
+int odsgd_set_warmup(odsgd_handle *h, int64_t warmup_steps);
+
+/* Iteration counter (number of global updates taken); set it to resume a run. */
+int64_t odsgd_get_iteration(const odsgd_handle *h);
+int odsgd_set_iteration(odsgd_handle *h, int64_t iteration);
+
+/* Release the handle.  Does not touch device memory and does not synchronise:
+ * the caller must not free the workspace while enqueued kernels may still run. */
+int odsgd_destroy(odsgd_handle *h);
+
+/* Static description of an error code; for ODSGD_EHIP, of the last HIP error seen by this thread. */
+const char *odsgd_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ODSGD_H */

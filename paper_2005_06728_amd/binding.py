@@ -1,0 +1,223 @@
+"""ctypes binding of libodsgd.so (C ABI declared in include/odsgd.h).
+
+Argument marshalling only: every arithmetic step runs in the HIP kernels.
+PyTorch supplies device memory (tensors -> data_ptr) and the current stream.
+There is no fallback: if the library has not been built the first call raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+ODSGD_OK = 0
+ODSGD_EINVAL = -1
+ODSGD_EALIGN = -2
+ODSGD_EALIAS = -3
+ODSGD_ENOSPC = -4
+ODSGD_EHIP = -5
+ODSGD_ERANGE = -6
+ODSGD_MAX_WORKERS = 64
+
+
+class odsgd_hyper(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("local_lr", ctypes.c_float),
+                ("momentum", ctypes.c_float), ("weight_decay", ctypes.c_float),
+                ("grad_scale", ctypes.c_float)]
+
+
+class OdsgdError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__("%s failed: %d (%s)" % (where, code, odsgd_strerror(code)))
+
+
+def library_path():
+    return os.environ.get("ODSGD_LIB", os.path.join(_HERE, "libodsgd.so"))
+
+
+def lib():
+    """Load libodsgd.so (once) and declare the C signatures."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise RuntimeError(
+            "%s not found: build it first (python -m paper_2005_06728_amd.build); "
+            "there is no CPU fallback" % path)
+    L = ctypes.CDLL(path)
+    vp, i64p = ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64)
+    hp = ctypes.POINTER(odsgd_hyper)
+    L.odsgd_workspace_bytes.restype = ctypes.c_size_t
+    L.odsgd_workspace_bytes.argtypes = [ctypes.c_int, i64p, ctypes.c_int]
+    L.odsgd_init.restype = ctypes.c_int
+    L.odsgd_init.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64p, vp, vp, vp, vp,
+                             ctypes.c_int, vp, ctypes.c_size_t, vp]
+    L.odsgd_local_update.restype = ctypes.c_int
+    L.odsgd_local_update.argtypes = [vp, ctypes.c_int, hp, vp]
+    for name in ("odsgd_global_update", "odsgd_step", "odsgd_ssgd_step"):
+        fn = getattr(L, name)
+        fn.restype = ctypes.c_int
+        fn.argtypes = [vp, hp, vp]
+    L.odsgd_set_warmup.restype = ctypes.c_int
+    L.odsgd_set_warmup.argtypes = [vp, ctypes.c_int64]
+    L.odsgd_get_iteration.restype = ctypes.c_int64
+    L.odsgd_get_iteration.argtypes = [vp]
+    L.odsgd_set_iteration.restype = ctypes.c_int
+    L.odsgd_set_iteration.argtypes = [vp, ctypes.c_int64]
+    L.odsgd_destroy.restype = ctypes.c_int
+    L.odsgd_destroy.argtypes = [vp]
+    L.odsgd_strerror.restype = ctypes.c_char_p
+    L.odsgd_strerror.argtypes = [ctypes.c_int]
+    _LIB = L
+    return L
+
+
+def odsgd_strerror(code):
+    return lib().odsgd_strerror(int(code)).decode()
+
+
+def _i64_array(vals):
+    return (ctypes.c_int64 * len(vals))(*[int(v) for v in vals])
+
+
+def _ptr_row(ptrs):
+    return (ctypes.c_void_p * len(ptrs))(*[ctypes.c_void_p(int(p)) for p in ptrs])
+
+
+def _ptr_rows(rows):
+    """[W][K] integers -> (array of W pointers to arrays of K pointers, keep-alive list)."""
+    keep = [_ptr_row(r) for r in rows]
+    top = (ctypes.c_void_p * len(rows))(*[ctypes.cast(r, ctypes.c_void_p) for r in keep])
+    return top, keep
+
+
+def odsgd_workspace_bytes(numel, num_workers):
+    return int(lib().odsgd_workspace_bytes(len(numel), _i64_array(numel), int(num_workers)))
+
+
+def odsgd_init(numel, w_ptrs, mom_ptrs, grad_ptrs, local_ptrs, num_workers,
+               workspace_ptr, workspace_bytes, stream=0):
+    """Raw form: integers in, handle (int) out.  grad_ptrs/local_ptrs are [W][K]."""
+    out = ctypes.c_void_p()
+    g_top, g_keep = _ptr_rows(grad_ptrs)
+    u_top, u_keep = _ptr_rows(local_ptrs)
+    w_row, m_row, n_arr = _ptr_row(w_ptrs), _ptr_row(mom_ptrs), _i64_array(numel)
+    rc = lib().odsgd_init(ctypes.byref(out), len(numel), n_arr,
+                          ctypes.cast(w_row, ctypes.c_void_p), ctypes.cast(m_row, ctypes.c_void_p),
+                          ctypes.cast(g_top, ctypes.c_void_p), ctypes.cast(u_top, ctypes.c_void_p),
+                          int(num_workers), ctypes.c_void_p(int(workspace_ptr)),
+                          int(workspace_bytes), ctypes.c_void_p(int(stream)))
+    del g_keep, u_keep, w_row, m_row, n_arr
+    if rc != ODSGD_OK:
+        raise OdsgdError(rc, "odsgd_init")
+    return out.value
+
+
+def _hyper(h):
+    if isinstance(h, odsgd_hyper):
+        return h
+    return odsgd_hyper(*[float(x) for x in h])
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream
+    return int(stream)
+
+
+def _call(name, rc):
+    if rc != ODSGD_OK:
+        raise OdsgdError(rc, name)
+
+
+def odsgd_local_update(handle, worker, hyper, stream=None):
+    _call("odsgd_local_update",
+          lib().odsgd_local_update(handle, int(worker), ctypes.byref(_hyper(hyper)), _stream(stream)))
+
+
+def odsgd_global_update(handle, hyper, stream=None):
+    _call("odsgd_global_update",
+          lib().odsgd_global_update(handle, ctypes.byref(_hyper(hyper)), _stream(stream)))
+
+
+def odsgd_step(handle, hyper, stream=None):
+    _call("odsgd_step", lib().odsgd_step(handle, ctypes.byref(_hyper(hyper)), _stream(stream)))
+
+
+def odsgd_ssgd_step(handle, hyper, stream=None):
+    _call("odsgd_ssgd_step",
+          lib().odsgd_ssgd_step(handle, ctypes.byref(_hyper(hyper)), _stream(stream)))
+
+
+def odsgd_set_warmup(handle, warmup_steps):
+    _call("odsgd_set_warmup", lib().odsgd_set_warmup(handle, int(warmup_steps)))
+
+
+def odsgd_get_iteration(handle):
+    return int(lib().odsgd_get_iteration(handle))
+
+
+def odsgd_set_iteration(handle, iteration):
+    _call("odsgd_set_iteration", lib().odsgd_set_iteration(handle, int(iteration)))
+
+
+def odsgd_destroy(handle):
+    _call("odsgd_destroy", lib().odsgd_destroy(handle))
+
+
+class Engine:
+    """Convenience owner of a handle: keeps the registered tensors and the
+    workspace alive and forwards to the C entry points of the same name."""
+
+    def __init__(self, w, mom, grads, local_w, warmup_steps=0, stream=None):
+        self.w, self.mom, self.grads, self.local_w = w, mom, grads, local_w
+        W = len(grads)
+        for t in list(w) + list(mom) + [x for r in grads for x in r] + [x for r in local_w for x in r]:
+            if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+                raise ValueError("tensors must be contiguous fp32 CUDA tensors")
+        numel = [t.numel() for t in w]
+        nbytes = odsgd_workspace_bytes(numel, W)
+        if nbytes == 0:
+            raise OdsgdError(ODSGD_EINVAL, "odsgd_workspace_bytes")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=w[0].device)
+        self.handle = odsgd_init(
+            numel, [t.data_ptr() for t in w], [t.data_ptr() for t in mom],
+            [[t.data_ptr() for t in r] for r in grads],
+            [[t.data_ptr() for t in r] for r in local_w],
+            W, self.workspace.data_ptr(), nbytes, _stream(stream))
+        if warmup_steps:
+            odsgd_set_warmup(self.handle, warmup_steps)
+
+    def step(self, hyper, stream=None):
+        odsgd_step(self.handle, hyper, stream)
+
+    def ssgd_step(self, hyper, stream=None):
+        odsgd_ssgd_step(self.handle, hyper, stream)
+
+    def local_update(self, worker, hyper, stream=None):
+        odsgd_local_update(self.handle, worker, hyper, stream)
+
+    def global_update(self, hyper, stream=None):
+        odsgd_global_update(self.handle, hyper, stream)
+
+    @property
+    def iteration(self):
+        return odsgd_get_iteration(self.handle)
+
+    def close(self):
+        if self.handle is not None:
+            torch.cuda.synchronize()
+            odsgd_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

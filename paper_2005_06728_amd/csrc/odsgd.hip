@@ -1,0 +1,686 @@
+// OD-SGD parameter-update engine for MI355X (gfx950): kernels and C ABI.
+//
+// One launch covers every parameter tensor ("multi-tensor apply"): odsgd_init
+// cuts the K tensors into fixed-size chunks and writes, into caller-provided
+// device memory, a chunk table (which tensor, where, how many elements) and a
+// pointer table (2 + 2W device pointers per tensor).  A workgroup takes a chunk,
+// fetches its descriptor and pointers with scalar loads, and streams the chunk
+// with 128-bit loads and stores.  The work is purely element-wise (about half a
+// flop per byte), so the only roofline that matters is HBM bandwidth; there is
+// no data reuse, hence no LDS staging and no matrix-core use.
+//
+// Arithmetic (paper: Section 3.1, Algorithms 1 and 2; Section 3.3 Local Updater):
+// see include/odsgd.h.  Every statement in the update_* functions below is one
+// binary32 operation; FP contraction is disabled for the whole file so that no
+// multiply-add pair is fused and results are independent of launch shape.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "odsgd.h"
+
+#pragma clang fp contract(off)
+
+namespace {
+
+// ---------------------------------------------------------------------------
+// compile-time tuning knobs (overridable with -D for sweeps)
+// ---------------------------------------------------------------------------
+#ifndef ODSGD_BLOCK
+#define ODSGD_BLOCK 256  // threads per workgroup (4 wavefronts)
+#endif
+#ifndef ODSGD_NT_GRAD
+#define ODSGD_NT_GRAD 1  // gradients are read once: non-temporal loads
+#endif
+#ifndef ODSGD_NT_LOCAL
+#define ODSGD_NT_LOCAL 1  // local weights are written once: non-temporal stores
+#endif
+#ifndef ODSGD_NT_STATE
+#define ODSGD_NT_STATE 1  // w, momentum: next touched one whole step later
+#endif
+#ifndef ODSGD_UNROLL_SMALL_W
+#define ODSGD_UNROLL_SMALL_W 2  // 128-bit groups in flight per lane when W <= 4
+#endif
+#ifndef ODSGD_UNROLL_MID_W
+#define ODSGD_UNROLL_MID_W 2  // ... when 4 < W <= 8
+#endif
+#ifndef ODSGD_UNROLL_BIG_W
+#define ODSGD_UNROLL_BIG_W 1  // ... when W > 8
+#endif
+
+constexpr int kBlock = ODSGD_BLOCK;
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+
+// Data pointers come out of the pointer table as integers.  Giving them the
+// global address space (instead of the generic one an integer-to-pointer cast
+// would have) lets the compiler emit global_load/global_store with a uniform
+// SGPR base and one shared 32-bit VGPR offset, rather than flat accesses with a
+// 64-bit VGPR address per array.
+#define ODSGD_GLOBAL_AS __attribute__((address_space(1)))
+template <typename T>
+using gptr = ODSGD_GLOBAL_AS T *;
+template <typename T>
+using gcptr = const ODSGD_GLOBAL_AS T *;
+
+// Tables live in global memory but never change while a kernel runs; reading
+// them through the constant address space makes the compiler use scalar loads
+// (one fetch per wavefront, results in SGPRs, usable as the uniform base of
+// "SGPR base + VGPR offset" global loads).
+#define ODSGD_CONST_AS __attribute__((address_space(4)))
+typedef const ODSGD_CONST_AS u4 *chunk_table_t;
+typedef const ODSGD_CONST_AS uint64_t *ptr_table_t;
+
+enum Mode : int {
+    MODE_OD = 0,      // local update of all workers from w_t, then global update
+    MODE_SSGD = 1,    // global update, then every worker receives w_{t+1}
+    MODE_GLOBAL = 2,  // global update only
+    MODE_LOCAL = 3,   // local update only, workers [wfirst, wfirst + wcount)
+};
+
+struct KernelArgs {
+    const void *chunks;  // device: nchunks * 16 bytes
+    const void *ptrs;    // device: K rows of (2 + 2*wtot) pointers
+    int nchunks;
+    int wtot;    // workers registered (row stride = 2 + 2*wtot)
+    int wfirst;  // first worker this launch touches
+    int wcount;  // number of workers this launch touches (== W_T when W_T > 0)
+    float lr, local_lr, momentum, weight_decay, grad_scale;
+};
+
+// chunk descriptor, 16 bytes: {tensor | vec<<31, count, offset_lo, offset_hi}
+constexpr uint32_t kVecFlag = 0x80000000u;
+
+// ---------------------------------------------------------------------------
+// memory access helpers
+// ---------------------------------------------------------------------------
+// `base` is a uniform 64-bit address (held in SGPRs), `idx` the lane's element
+// index in units of T.  The byte offset is formed in 32 bits (chunks are at
+// most 2^24 elements), which is what allows the SGPR-base + VGPR-offset form.
+template <bool NT, typename T>
+__device__ __forceinline__ T load(uint64_t base, unsigned idx)
+{
+    const gcptr<T> p = (gcptr<T>)((gcptr<char>)base + idx * (unsigned)sizeof(T));
+    if constexpr (NT)
+        return __builtin_nontemporal_load(p);
+    else
+        return *p;
+}
+
+template <bool NT, typename T>
+__device__ __forceinline__ void store(uint64_t base, unsigned idx, T x)
+{
+    const gptr<T> p = (gptr<T>)((gptr<char>)base + idx * (unsigned)sizeof(T));
+    if constexpr (NT)
+        __builtin_nontemporal_store(x, p);
+    else
+        *p = x;
+}
+
+// ---------------------------------------------------------------------------
+// the update rules; T is float or f4 (element-wise)
+// ---------------------------------------------------------------------------
+struct Hyp {
+    float lr, local_lr, momentum, weight_decay, grad_scale;
+};
+
+// u_m = w_t - local_lr * (g_m + r)
+template <typename T>
+__device__ __forceinline__ T update_local(T w0, T g, T r, float local_lr)
+{
+    T dm = g + r;
+    T pm = local_lr * dm;
+    return w0 - pm;
+}
+
+// v' = momentum * v_t - lr * (s * grad_scale + r);  w' = w_t + v'
+template <typename T>
+__device__ __forceinline__ void update_global(T w0, T v0, T s, T r, const Hyp &h, T &w1, T &v1)
+{
+    T gb = s * h.grad_scale;
+    T d = gb + r;
+    T a = h.momentum * v0;
+    T b = h.lr * d;
+    v1 = a - b;
+    w1 = w0 + v1;
+}
+
+// ---------------------------------------------------------------------------
+// one chunk, fixed worker count W_T: U groups in flight per lane, every load
+// issued before the first store (the compiler cannot prove the outputs do not
+// alias the inputs, so the order is written out by hand).
+// ---------------------------------------------------------------------------
+template <int W_T, int MODE>
+struct Ptrs {
+    uint64_t w;
+    uint64_t v;
+    uint64_t g[W_T];
+    uint64_t u[W_T];
+};
+
+template <int W_T, int MODE, int U, typename T>
+__device__ __forceinline__ void apply_fixed(const Ptrs<W_T, MODE> &p, unsigned i, const Hyp &h)
+{
+    constexpr bool need_v = (MODE != MODE_LOCAL);
+    constexpr bool need_u = (MODE != MODE_GLOBAL);
+    T w0[U], v0[U], g[U][W_T];
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+        w0[j] = load<ODSGD_NT_STATE, T>(p.w, i + j * kBlock);
+        if constexpr (need_v)
+            v0[j] = load<ODSGD_NT_STATE, T>(p.v, i + j * kBlock);
+#pragma unroll
+        for (int m = 0; m < W_T; ++m)
+            g[j][m] = load<ODSGD_NT_GRAD, T>(p.g[m], i + j * kBlock);
+    }
+
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+        T r = h.weight_decay * w0[j];
+        T w1 = w0[j], v1;
+        if constexpr (MODE != MODE_LOCAL) {
+            T s = g[j][0];
+#pragma unroll
+            for (int m = 1; m < W_T; ++m)
+                s = s + g[j][m];
+            update_global(w0[j], v0[j], s, r, h, w1, v1);
+        }
+        if constexpr (need_u) {
+#pragma unroll
+            for (int m = 0; m < W_T; ++m) {
+                T um = (MODE == MODE_SSGD) ? w1 : update_local(w0[j], g[j][m], r, h.local_lr);
+                store<ODSGD_NT_LOCAL, T>(p.u[m], i + j * kBlock, um);
+            }
+        }
+        if constexpr (MODE != MODE_LOCAL) {
+            store<ODSGD_NT_STATE, T>(p.v, i + j * kBlock, v1);
+            store<ODSGD_NT_STATE, T>(p.w, i + j * kBlock, w1);
+        }
+    }
+}
+
+// any worker count: pointers are fetched from the table inside the worker loop
+template <int MODE, typename T>
+__device__ __forceinline__ void apply_generic(ptr_table_t row, uint64_t byte_off, int wtot, int wfirst,
+                                              int wcount, unsigned i, const Hyp &h)
+{
+    const uint64_t pw = row[0] + byte_off;
+    const uint64_t pv = row[1] + byte_off;
+    T w0 = load<ODSGD_NT_STATE, T>(pw, i);
+    T r = h.weight_decay * w0;
+    T s;
+    for (int m = 0; m < wcount; ++m) {
+        T gm = load<ODSGD_NT_GRAD, T>(row[2 + wfirst + m] + byte_off, i);
+        s = (m == 0) ? gm : s + gm;
+        if constexpr (MODE == MODE_OD || MODE == MODE_LOCAL) {
+            store<ODSGD_NT_LOCAL, T>(row[2 + wtot + wfirst + m] + byte_off, i,
+                                     update_local(w0, gm, r, h.local_lr));
+        }
+    }
+    if constexpr (MODE != MODE_LOCAL) {
+        T v0 = load<ODSGD_NT_STATE, T>(pv, i);
+        T w1, v1;
+        update_global(w0, v0, s, r, h, w1, v1);
+        if constexpr (MODE == MODE_SSGD) {
+            for (int m = 0; m < wcount; ++m) {
+                store<ODSGD_NT_LOCAL, T>(row[2 + wtot + wfirst + m] + byte_off, i, w1);
+            }
+        }
+        store<ODSGD_NT_STATE, T>(pv, i, v1);
+        store<ODSGD_NT_STATE, T>(pw, i, w1);
+    }
+}
+
+template <int W_T>
+constexpr int unroll_for()
+{
+    return W_T <= 4 ? ODSGD_UNROLL_SMALL_W : (W_T <= 8 ? ODSGD_UNROLL_MID_W : ODSGD_UNROLL_BIG_W);
+}
+
+// ---------------------------------------------------------------------------
+// the kernel: grid-stride over the chunk table
+// ---------------------------------------------------------------------------
+template <int W_T, int MODE>
+__global__ void __launch_bounds__(kBlock) odsgd_kernel(KernelArgs a)
+{
+    const chunk_table_t chunks = (chunk_table_t)a.chunks;
+    const ptr_table_t ptrs = (ptr_table_t)a.ptrs;
+    const Hyp h{a.lr, a.local_lr, a.momentum, a.weight_decay, a.grad_scale};
+    const unsigned tid = threadIdx.x;
+    const int stride = 2 + 2 * a.wtot;
+
+    for (int c = blockIdx.x; c < a.nchunks; c += gridDim.x) {
+        const u4 d = chunks[c];
+        const uint32_t tensor = d.x & ~kVecFlag;
+        const bool vec = (d.x & kVecFlag) != 0;
+        const unsigned count = d.y;
+        const uint64_t byte_off = (((uint64_t)d.w << 32) | d.z) * sizeof(float);
+        const ptr_table_t row = ptrs + (uint64_t)tensor * stride;
+        const unsigned nvec = vec ? (count >> 2) : 0u;
+
+        if constexpr (W_T > 0) {
+            Ptrs<W_T, MODE> p;
+            p.w = row[0] + byte_off;
+            p.v = row[1] + byte_off;
+#pragma unroll
+            for (int m = 0; m < W_T; ++m) {
+                p.g[m] = row[2 + a.wfirst + m] + byte_off;
+                p.u[m] = row[2 + a.wtot + a.wfirst + m] + byte_off;
+            }
+            constexpr int U = unroll_for<W_T>();
+            unsigned i = tid;
+            if constexpr (U > 1) {
+                for (; i + (U - 1) * kBlock < nvec; i += U * kBlock)
+                    apply_fixed<W_T, MODE, U, f4>(p, i, h);
+            }
+            for (; i < nvec; i += kBlock)
+                apply_fixed<W_T, MODE, 1, f4>(p, i, h);
+            for (unsigned t = nvec * 4 + tid; t < count; t += kBlock)
+                apply_fixed<W_T, MODE, 1, float>(p, t, h);
+        } else {
+            for (unsigned i = tid; i < nvec; i += kBlock)
+                apply_generic<MODE, f4>(row, byte_off, a.wtot, a.wfirst, a.wcount, i, h);
+            for (unsigned t = nvec * 4 + tid; t < count; t += kBlock)
+                apply_generic<MODE, float>(row, byte_off, a.wtot, a.wfirst, a.wcount, t, h);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+thread_local hipError_t g_last_hip_error = hipSuccess;
+
+struct Tuning {
+    int64_t chunk_elems;  // elements per chunk (multiple of 4 * kBlock)
+    int blocks_per_cu;    // grid cap = blocks_per_cu * CUs; 0 = one workgroup per chunk
+};
+
+int64_t env_int(const char *name, int64_t dflt)
+{
+    const char *s = std::getenv(name);
+    if (!s || !*s)
+        return dflt;
+    char *end = nullptr;
+    long long v = std::strtoll(s, &end, 10);
+    return (end && *end == '\0') ? (int64_t)v : dflt;
+}
+
+Tuning current_tuning()
+{
+    Tuning t;
+    t.chunk_elems = env_int("ODSGD_CHUNK_ELEMS", 4096);
+    const int64_t q = 4 * kBlock;
+    if (t.chunk_elems < q)
+        t.chunk_elems = q;
+    if (t.chunk_elems > (int64_t)1 << 24)
+        t.chunk_elems = (int64_t)1 << 24;
+    t.chunk_elems = (t.chunk_elems / q) * q;
+    t.blocks_per_cu = (int)env_int("ODSGD_BLOCKS_PER_CU", 0);
+    if (t.blocks_per_cu < 0)
+        t.blocks_per_cu = 0;
+    return t;
+}
+
+constexpr int64_t kMaxNumel = (int64_t)1 << 40;
+constexpr int64_t kMaxChunks = 0x7ffffffe;
+
+// number of chunks for this tensor list, or -1 on invalid input / overflow
+int64_t count_chunks(int num_tensors, const int64_t *numel, int64_t chunk_elems, int *err)
+{
+    int64_t n = 0;
+    for (int k = 0; k < num_tensors; ++k) {
+        if (numel[k] < 0) {
+            *err = ODSGD_EINVAL;
+            return -1;
+        }
+        if (numel[k] >= kMaxNumel) {
+            *err = ODSGD_ERANGE;
+            return -1;
+        }
+        n += (numel[k] + chunk_elems - 1) / chunk_elems;
+        if (n > kMaxChunks) {
+            *err = ODSGD_ERANGE;
+            return -1;
+        }
+    }
+    return n;
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+size_t ptr_table_bytes(int num_tensors, int num_workers)
+{
+    return align_up((size_t)num_tensors * (2 + 2 * (size_t)num_workers) * sizeof(uint64_t), 256);
+}
+
+struct Range {
+    uintptr_t lo, hi;
+    bool is_output;
+};
+
+// true if any output range overlaps any other range
+bool ranges_alias(std::vector<Range> &r)
+{
+    std::sort(r.begin(), r.end(), [](const Range &a, const Range &b) { return a.lo < b.lo; });
+    uintptr_t max_hi_any = 0, max_hi_out = 0;
+    for (const Range &x : r) {
+        if (x.lo < max_hi_out)
+            return true;
+        if (x.is_output && x.lo < max_hi_any)
+            return true;
+        max_hi_any = std::max(max_hi_any, x.hi);
+        if (x.is_output)
+            max_hi_out = std::max(max_hi_out, x.hi);
+    }
+    return false;
+}
+
+using KernelFn = void (*)(KernelArgs);
+
+template <int MODE>
+KernelFn pick_kernel(int wcount)
+{
+    switch (wcount) {
+    case 1: return odsgd_kernel<1, MODE>;
+    case 2: return odsgd_kernel<2, MODE>;
+    case 4: return odsgd_kernel<4, MODE>;
+    case 8: return odsgd_kernel<8, MODE>;
+    case 12: return odsgd_kernel<12, MODE>;
+    case 16: return odsgd_kernel<16, MODE>;
+    default: return odsgd_kernel<0, MODE>;
+    }
+}
+
+KernelFn pick_kernel(int mode, int wcount)
+{
+    switch (mode) {
+    case MODE_OD: return pick_kernel<MODE_OD>(wcount);
+    case MODE_SSGD: return pick_kernel<MODE_SSGD>(wcount);
+    case MODE_GLOBAL: return pick_kernel<MODE_GLOBAL>(wcount);
+    default: return pick_kernel<MODE_LOCAL>(wcount);
+    }
+}
+
+}  // namespace
+
+struct odsgd_handle {
+    int num_tensors;
+    int num_workers;
+    int64_t nchunks;
+    const void *d_chunks;
+    const void *d_ptrs;
+    int device;
+    int num_cus;
+    Tuning tuning;
+    int64_t iteration;
+    int64_t warmup_steps;
+    std::vector<unsigned char> staging;  // host image of the tables (kept alive for the upload)
+};
+
+namespace {
+
+int launch(odsgd_handle *h, int mode, int wfirst, int wcount, const odsgd_hyper *hy, void *stream)
+{
+    if (h->nchunks == 0)
+        return ODSGD_OK;
+    KernelArgs a;
+    a.chunks = h->d_chunks;
+    a.ptrs = h->d_ptrs;
+    a.nchunks = (int)h->nchunks;
+    a.wtot = h->num_workers;
+    a.wfirst = wfirst;
+    a.wcount = wcount;
+    a.lr = hy->lr;
+    a.local_lr = hy->local_lr;
+    a.momentum = hy->momentum;
+    a.weight_decay = hy->weight_decay;
+    a.grad_scale = (hy->grad_scale <= 0.0f) ? 1.0f / (float)h->num_workers : hy->grad_scale;
+
+    int64_t grid = h->nchunks;
+    if (h->tuning.blocks_per_cu > 0)
+        grid = std::min<int64_t>(grid, (int64_t)h->tuning.blocks_per_cu * h->num_cus);
+    KernelFn fn = pick_kernel(mode, wcount);
+    hipLaunchKernelGGL(fn, dim3((unsigned)grid), dim3(kBlock), 0, (hipStream_t)stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        g_last_hip_error = e;
+        return ODSGD_EHIP;
+    }
+    return ODSGD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t odsgd_workspace_bytes(int num_tensors, const int64_t *numel, int num_workers)
+{
+    if (num_tensors < 1 || !numel || num_workers < 1 || num_workers > ODSGD_MAX_WORKERS)
+        return 0;
+    int err = 0;
+    const Tuning t = current_tuning();
+    const int64_t nchunks = count_chunks(num_tensors, numel, t.chunk_elems, &err);
+    if (nchunks < 0)
+        return 0;
+    return ptr_table_bytes(num_tensors, num_workers) + align_up((size_t)std::max<int64_t>(nchunks, 1) * 16, 256);
+}
+
+int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel, float *const *w,
+               float *const *mom, const float *const *const *grads, float *const *const *local_w,
+               int num_workers, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!out)
+        return ODSGD_EINVAL;
+    *out = nullptr;
+    if (num_tensors < 1 || !numel || !w || !mom || !grads || !local_w || num_workers < 1 ||
+        num_workers > ODSGD_MAX_WORKERS || !workspace)
+        return ODSGD_EINVAL;
+    for (int m = 0; m < num_workers; ++m)
+        if (!grads[m] || !local_w[m])
+            return ODSGD_EINVAL;
+
+    const Tuning tuning = current_tuning();
+    int err = 0;
+    const int64_t nchunks = count_chunks(num_tensors, numel, tuning.chunk_elems, &err);
+    if (nchunks < 0)
+        return err;
+
+    const int W = num_workers;
+    const int stride = 2 + 2 * W;
+
+    // pointer checks: non-null and 4-byte aligned where the tensor is not empty
+    std::vector<Range> ranges;
+    ranges.reserve((size_t)num_tensors * stride);
+    std::vector<unsigned char> vec_ok(num_tensors, 1);
+    for (int k = 0; k < num_tensors; ++k) {
+        if (numel[k] == 0)
+            continue;
+        const size_t bytes = (size_t)numel[k] * sizeof(float);
+        for (int j = 0; j < stride; ++j) {
+            const void *p = j == 0   ? (const void *)w[k]
+                            : j == 1 ? (const void *)mom[k]
+                            : j < 2 + W ? (const void *)grads[j - 2][k]
+                                        : (const void *)local_w[j - 2 - W][k];
+            if (!p)
+                return ODSGD_EINVAL;
+            const uintptr_t a = (uintptr_t)p;
+            if (a % 4 != 0)
+                return ODSGD_EALIGN;
+            if (a % 16 != 0)
+                vec_ok[k] = 0;
+            const bool is_output = (j < 2) || (j >= 2 + W);
+            ranges.push_back(Range{a, a + bytes, is_output});
+        }
+    }
+    if ((uintptr_t)workspace % 256 != 0)
+        return ODSGD_EALIGN;
+    const size_t ptr_bytes = ptr_table_bytes(num_tensors, W);
+    const size_t chunk_bytes = align_up((size_t)std::max<int64_t>(nchunks, 1) * 16, 256);
+    if (workspace_bytes < ptr_bytes + chunk_bytes)
+        return ODSGD_ENOSPC;
+    ranges.push_back(Range{(uintptr_t)workspace, (uintptr_t)workspace + ptr_bytes + chunk_bytes, true});
+    if (ranges_alias(ranges))
+        return ODSGD_EALIAS;
+
+    odsgd_handle *h = new (std::nothrow) odsgd_handle();
+    if (!h)
+        return ODSGD_EINVAL;
+    h->num_tensors = num_tensors;
+    h->num_workers = W;
+    h->nchunks = nchunks;
+    h->tuning = tuning;
+    h->iteration = 0;
+    h->warmup_steps = 0;
+    h->d_ptrs = workspace;
+    h->d_chunks = (const unsigned char *)workspace + ptr_bytes;
+
+    hipError_t e = hipGetDevice(&h->device);
+    if (e == hipSuccess) {
+        int cus = 0;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device);
+        h->num_cus = cus > 0 ? cus : 256;
+    }
+    if (e != hipSuccess) {
+        g_last_hip_error = e;
+        delete h;
+        return ODSGD_EHIP;
+    }
+
+    // host image of both tables
+    h->staging.assign(ptr_bytes + chunk_bytes, 0);
+    uint64_t *pt = reinterpret_cast<uint64_t *>(h->staging.data());
+    for (int k = 0; k < num_tensors; ++k) {
+        uint64_t *row = pt + (size_t)k * stride;
+        row[0] = (uint64_t)(uintptr_t)w[k];
+        row[1] = (uint64_t)(uintptr_t)mom[k];
+        for (int m = 0; m < W; ++m) {
+            row[2 + m] = (uint64_t)(uintptr_t)grads[m][k];
+            row[2 + W + m] = (uint64_t)(uintptr_t)local_w[m][k];
+        }
+    }
+    // chunk table: full chunks of all tensors first, ragged last chunks after
+    // them, so the short pieces fill the end of the launch
+    uint32_t *ct = reinterpret_cast<uint32_t *>(h->staging.data() + ptr_bytes);
+    int64_t c = 0;
+    const int64_t C = tuning.chunk_elems;
+    for (int pass = 0; pass < 2; ++pass) {
+        for (int k = 0; k < num_tensors; ++k) {
+            const int64_t n = numel[k];
+            const int64_t nfull = n / C;
+            const int64_t lo = pass == 0 ? 0 : nfull;
+            const int64_t hi = pass == 0 ? nfull : (n + C - 1) / C;
+            for (int64_t j = lo; j < hi; ++j) {
+                const int64_t off = j * C;
+                const int64_t cnt = std::min<int64_t>(C, n - off);
+                uint32_t *dsc = ct + c * 4;
+                dsc[0] = (uint32_t)k | (vec_ok[k] ? kVecFlag : 0u);
+                dsc[1] = (uint32_t)cnt;
+                dsc[2] = (uint32_t)((uint64_t)off & 0xffffffffu);
+                dsc[3] = (uint32_t)((uint64_t)off >> 32);
+                ++c;
+            }
+        }
+    }
+
+    e = hipMemcpyAsync(workspace, h->staging.data(), h->staging.size(), hipMemcpyHostToDevice,
+                       (hipStream_t)stream);
+    if (e == hipSuccess)
+        e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) {
+        g_last_hip_error = e;
+        delete h;
+        return ODSGD_EHIP;
+    }
+    std::vector<unsigned char>().swap(h->staging);
+    *out = h;
+    return ODSGD_OK;
+}
+
+int odsgd_local_update(odsgd_handle *h, int worker, const odsgd_hyper *hyper, void *stream)
+{
+    if (!h || !hyper || worker < -1 || worker >= h->num_workers)
+        return ODSGD_EINVAL;
+    if (worker < 0)
+        return launch(h, MODE_LOCAL, 0, h->num_workers, hyper, stream);
+    return launch(h, MODE_LOCAL, worker, 1, hyper, stream);
+}
+
+int odsgd_global_update(odsgd_handle *h, const odsgd_hyper *hyper, void *stream)
+{
+    if (!h || !hyper)
+        return ODSGD_EINVAL;
+    int rc = launch(h, MODE_GLOBAL, 0, h->num_workers, hyper, stream);
+    if (rc == ODSGD_OK)
+        ++h->iteration;
+    return rc;
+}
+
+int odsgd_ssgd_step(odsgd_handle *h, const odsgd_hyper *hyper, void *stream)
+{
+    if (!h || !hyper)
+        return ODSGD_EINVAL;
+    int rc = launch(h, MODE_SSGD, 0, h->num_workers, hyper, stream);
+    if (rc == ODSGD_OK)
+        ++h->iteration;
+    return rc;
+}
+
+int odsgd_step(odsgd_handle *h, const odsgd_hyper *hyper, void *stream)
+{
+    if (!h || !hyper)
+        return ODSGD_EINVAL;
+    const int mode = (h->iteration < h->warmup_steps) ? MODE_SSGD : MODE_OD;
+    int rc = launch(h, mode, 0, h->num_workers, hyper, stream);
+    if (rc == ODSGD_OK)
+        ++h->iteration;
+    return rc;
+}
+
+int odsgd_set_warmup(odsgd_handle *h, int64_t warmup_steps)
+{
+    if (!h || warmup_steps < 0)
+        return ODSGD_EINVAL;
+    h->warmup_steps = warmup_steps;
+    return ODSGD_OK;
+}
+
+int64_t odsgd_get_iteration(const odsgd_handle *h) { return h ? h->iteration : (int64_t)ODSGD_EINVAL; }
+
+int odsgd_set_iteration(odsgd_handle *h, int64_t iteration)
+{
+    if (!h || iteration < 0)
+        return ODSGD_EINVAL;
+    h->iteration = iteration;
+    return ODSGD_OK;
+}
+
+int odsgd_destroy(odsgd_handle *h)
+{
+    if (!h)
+        return ODSGD_EINVAL;
+    delete h;
+    return ODSGD_OK;
+}
+
+const char *odsgd_strerror(int code)
+{
+    switch (code) {
+    case ODSGD_OK: return "success";
+    case ODSGD_EINVAL: return "invalid argument";
+    case ODSGD_EALIGN: return "device pointer not sufficiently aligned";
+    case ODSGD_EALIAS: return "an output buffer overlaps another registered buffer";
+    case ODSGD_ENOSPC: return "workspace too small";
+    case ODSGD_EHIP: return hipGetErrorString(g_last_hip_error);
+    case ODSGD_ERANGE: return "tensor list too large for the chunk table";
+    default: return "unknown error code";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,101 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol the header declares, sizes its workspace consistently and rejects
+bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+from paper_2005_06728_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "odsgd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(odsgd_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_symbols()
+    assert {"odsgd_init", "odsgd_global_update", "odsgd_local_update", "odsgd_step"} <= set(names)
+    L = ctypes.CDLL(B.library_path())
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_binding_has_the_same_names():
+    for n in _declared_symbols():
+        assert hasattr(B, n), n
+
+
+def test_strerror():
+    assert B.odsgd_strerror(0) == "success"
+    for code in (B.ODSGD_EINVAL, B.ODSGD_EALIGN, B.ODSGD_EALIAS, B.ODSGD_ENOSPC, B.ODSGD_ERANGE):
+        assert B.odsgd_strerror(code) not in ("", "success", "unknown error code")
+    assert B.odsgd_strerror(-99) == "unknown error code"
+
+
+def test_workspace_bytes():
+    assert B.odsgd_workspace_bytes([10], 0) == 0
+    assert B.odsgd_workspace_bytes([10], B.ODSGD_MAX_WORKERS + 1) == 0
+    assert B.odsgd_workspace_bytes([-1], 2) == 0
+    assert B.odsgd_workspace_bytes([1 << 40], 2) == 0
+    small = B.odsgd_workspace_bytes([10, 0, 5], 4)
+    assert small > 0 and small % 256 == 0
+    # pointer table grows with K*(2+2W), chunk table with the number of chunks
+    assert B.odsgd_workspace_bytes([10] * 100, 16) >= 100 * 34 * 8
+    big = B.odsgd_workspace_bytes([102760448], 16)
+    assert big > B.odsgd_workspace_bytes([1000], 16)
+
+
+def test_init_rejects_bad_arguments_without_a_device():
+    good = dict(numel=[8], w_ptrs=[0x1000], mom_ptrs=[0x2000], grad_ptrs=[[0x3000]],
+                local_ptrs=[[0x4000]], num_workers=1, workspace_ptr=0x10000, workspace_bytes=1 << 20)
+
+    def expect(code, **kw):
+        args = dict(good)
+        args.update(kw)
+        with pytest.raises(B.OdsgdError) as e:
+            B.odsgd_init(**args)
+        assert e.value.code == code, (e.value.code, kw)
+
+    expect(B.ODSGD_EINVAL, w_ptrs=[0])                         # null weight pointer
+    expect(B.ODSGD_EINVAL, num_workers=0, grad_ptrs=[], local_ptrs=[])
+    expect(B.ODSGD_EINVAL, numel=[-3])
+    expect(B.ODSGD_EINVAL, workspace_ptr=0)
+    expect(B.ODSGD_ERANGE, numel=[1 << 40])
+    expect(B.ODSGD_EALIGN, mom_ptrs=[0x2002])                  # not 4-byte aligned
+    expect(B.ODSGD_EALIGN, workspace_ptr=0x10010)              # workspace not 256-byte aligned
+    expect(B.ODSGD_ENOSPC, workspace_bytes=16)
+    expect(B.ODSGD_EALIAS, local_ptrs=[[0x1010]])              # local weights inside w
+    expect(B.ODSGD_EALIAS, mom_ptrs=[0x1000])                  # momentum == w
+    expect(B.ODSGD_EALIAS, grad_ptrs=[[0x2010]])               # gradient inside momentum
+    expect(B.ODSGD_EALIAS, workspace_ptr=0x1000 - 0x100, workspace_bytes=1 << 20)
+    # gradients may alias one another; an empty tensor may carry null pointers
+    # (these get past validation and fail only because no device exists here;
+    # with a device present the made-up addresses must not reach it)
+    if torch.cuda.is_available():
+        return
+    for kw in (dict(num_workers=2, grad_ptrs=[[0x3000], [0x3000]], local_ptrs=[[0x4000], [0x5000]]),
+               dict(numel=[8, 0], w_ptrs=[0x1000, 0], mom_ptrs=[0x2000, 0], grad_ptrs=[[0x3000, 0]],
+                    local_ptrs=[[0x4000, 0]])):
+        args = dict(good)
+        args.update(kw)
+        with pytest.raises(B.OdsgdError) as e:
+            B.odsgd_init(**args)
+        assert e.value.code == B.ODSGD_EHIP
+
+
+def test_calls_reject_null_handle():
+    h = B.odsgd_hyper(0.1, 0.1, 0.9, 0.0, 0.0)
+    L = B.lib()
+    assert L.odsgd_step(None, ctypes.byref(h), None) == B.ODSGD_EINVAL
+    assert L.odsgd_global_update(None, ctypes.byref(h), None) == B.ODSGD_EINVAL
+    assert L.odsgd_local_update(None, 0, ctypes.byref(h), None) == B.ODSGD_EINVAL
+    assert L.odsgd_ssgd_step(None, ctypes.byref(h), None) == B.ODSGD_EINVAL
+    assert L.odsgd_destroy(None) == B.ODSGD_EINVAL
+    assert L.odsgd_set_warmup(None, 1) == B.ODSGD_EINVAL

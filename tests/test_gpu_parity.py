@@ -1,0 +1,377 @@
+"""GPU parity: the HIP path (called through the C ABI) against the CPU oracle,
+element by element, on the same seeded inputs.  Run with -m gpu on an MI355X."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from gpu_harness import (TOL, compare, f32, host_state, hyper_tuple, make_engine, oracle_hyper,
+                         refresh_host_grads, to_host)
+from helpers import cat, same_bits, split
+from oracle import odsgd_oracle as oracle
+from paper_2005_06728_amd import binding as B
+from paper_2005_06728_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+CANARY = 1234.5
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ---------------------------------------------------------------------------
+# custom tensor lists inside guarded arenas
+# ---------------------------------------------------------------------------
+class Arena:
+    """One flat buffer per role; tensors are views separated by canary gaps."""
+
+    def __init__(self, sizes, shift=0, gap=64):
+        offs, o = [], gap + shift
+        for n in sizes:
+            offs.append(o)
+            o += ((n + 3) // 4) * 4 + gap  # next view starts 16-byte aligned (+ shift elements)
+        self.buf = torch.full((o + gap,), CANARY, dtype=torch.float32, device=DEV)
+        self.views = [self.buf[a:a + n] for a, n in zip(offs, sizes)]
+        self.mask = torch.ones(o + gap, dtype=torch.bool, device=DEV)
+        for a, n in zip(offs, sizes):
+            self.mask[a:a + n] = False
+
+    def intact(self):
+        return bool(torch.all(self.buf[self.mask] == CANARY))
+
+
+def custom_state(sizes, W, seed, shifts=None, wstd=0.05, gstd=1e-3):
+    """shifts: per-role element shift (0 = 16-byte aligned views, 1..3 = only 4-byte aligned)."""
+    shifts = shifts or {}
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed)
+    arenas = {"w": Arena(sizes, shifts.get("w", 0)), "v": Arena(sizes, shifts.get("v", 0)),
+              "g": [Arena(sizes, shifts.get("g", 0)) for _ in range(W)],
+              "u": [Arena(sizes, shifts.get("u", 0)) for _ in range(W)]}
+    st = {"w": arenas["w"].views, "v": arenas["v"].views,
+          "g": [a.views for a in arenas["g"]], "u": [a.views for a in arenas["u"]]}
+    for t in st["w"]:
+        t.normal_(0, wstd, generator=gen)
+    for t in st["v"]:
+        t.normal_(0, 1e-3, generator=gen)
+    for m in range(W):
+        for t in st["g"][m]:
+            t.normal_(0, gstd, generator=gen)
+    return st, arenas, gen
+
+
+def arenas_intact(arenas):
+    return (arenas["w"].intact() and arenas["v"].intact()
+            and all(a.intact() for a in arenas["g"]) and all(a.intact() for a in arenas["u"]))
+
+
+def regen_grads(st, gen, gstd=1e-3):
+    for r in st["g"]:
+        for t in r:
+            t.normal_(0, gstd, generator=gen)
+
+
+RAGGED = [0, 1, 3, 4, 5, 1023, 1024, 1025, 4096, 4097, 8191, 3 * 4096 + 7, 20000]
+
+
+# ---------------------------------------------------------------------------
+# hand-expanded literals on the GPU
+# ---------------------------------------------------------------------------
+def test_hand_expanded_sequence_on_gpu(golden_w2):
+    gd = golden_w2
+    h = gd["hyper"]
+    sizes = gd["tensors"]
+    mk = lambda flat: [torch.tensor(a, device=DEV) for a in split(flat, sizes)]
+    st = {"w": mk(gd["w_init"]), "v": mk(gd["v_init"]),
+          "g": [mk([0, 0, 0]), mk([0, 0, 0])], "u": [mk([0, 0, 0]), mk([0, 0, 0])]}
+    eng = make_engine(st)
+    hy = (h["lr"], h["local_lr"], h["momentum"], h["weight_decay"], h["grad_scale"])
+    for it in gd["iters"]:
+        for m, key in enumerate(("g0", "g1")):
+            for t, a in zip(st["g"][m], split(it[key], sizes)):
+                t.copy_(torch.tensor(a))
+        eng.step(hy)
+        torch.cuda.synchronize()
+        assert cat(to_host(st["w"])).tolist() == it["w"]
+        assert cat(to_host(st["v"])).tolist() == it["v"]
+        assert cat(to_host(st["u"][0])).tolist() == it["u0"]
+        assert cat(to_host(st["u"][1])).tolist() == it["u1"]
+    assert eng.iteration == 3
+    eng.close()
+
+
+# ---------------------------------------------------------------------------
+# the five parameter sets, fused step, all outputs compared after every iteration
+# ---------------------------------------------------------------------------
+def run_workload(name, iterations, warmup=0):
+    w = wl.WORKLOADS[name]
+    say("workload %s: K=%d N=%d W=%d iterations=%d warmup=%d" %
+        (name, len(w.tensors), wl.total_params(w), w.num_workers, iterations, warmup))
+    st = wl.allocate(w, DEV)
+    hs = host_state(st)
+    eng = make_engine(st, warmup_steps=warmup)
+    hy = hyper_tuple(w.hyper)
+    oh = oracle_hyper(hy)
+    total_bad = 0
+    for it in range(iterations):
+        wl.fill_all_grads_(st, w, it)
+        refresh_host_grads(st, hs)
+        eng.step(hy)
+        oracle.step(it, warmup, hs["w"], hs["v"], hs["g"], hs["u"], **oh)
+        bad, worst = compare(st, hs, label="%s it %d" % (name, it))
+        total_bad += bad
+    say("  %s: %d elements differ bitwise from the oracle" % (name, total_bad))
+    eng.close()
+    return total_bad
+
+
+def test_lenet5_full_run():
+    assert run_workload("lenet5", wl.WORKLOADS["lenet5"].iterations) == 0
+
+
+def test_resnet20_full_run_heavy_tailed_gradients():
+    assert run_workload("resnet20", wl.WORKLOADS["resnet20"].iterations) == 0
+
+
+def test_resnet50_full_size():
+    assert run_workload("resnet50", 3) == 0
+
+
+def test_alexnet_full_size():
+    assert run_workload("alexnet", 2) == 0
+
+
+def test_vgg16_full_size_with_exact_zero_gradients():
+    assert run_workload("vgg16", 2) == 0
+
+
+def test_resnet20_with_warmup_schedule():
+    assert run_workload("resnet20", 8, warmup=3) == 0
+
+
+# ---------------------------------------------------------------------------
+# worker counts (templated and generic kernels), ragged sizes, guard bands
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("W", [1, 2, 3, 4, 5, 7, 8, 12, 16, 17])
+def test_worker_counts_ragged_sizes_all_entry_points(W):
+    say("W=%d sizes=%s" % (W, RAGGED))
+    st, arenas, gen = custom_state(RAGGED, W, seed=100 + W)
+    hs = host_state(st)
+    eng = make_engine(st)
+    hy = (0.05, 0.02, 0.9, 1e-3, 0.0 if W % 2 else 1.0 / W)
+    oh = oracle_hyper(hy)
+    # fused step
+    eng.step(hy)
+    oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], **oh)
+    assert compare(st, hs, label="fused")[0] == 0
+    # local(all) then global
+    regen_grads(st, gen)
+    refresh_host_grads(st, hs)
+    eng.local_update(-1, hy)
+    eng.global_update(hy)
+    oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], **oh)
+    assert compare(st, hs, label="local(all)+global")[0] == 0
+    # one worker at a time, then global
+    regen_grads(st, gen)
+    refresh_host_grads(st, hs)
+    for m in range(W):
+        eng.local_update(m, hy)
+    eng.global_update(hy)
+    oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], **oh)
+    assert compare(st, hs, label="local(m)+global")[0] == 0
+    # a single worker's local update touches only its own row
+    regen_grads(st, gen)
+    refresh_host_grads(st, hs)
+    eng.local_update(W - 1, hy)
+    oracle.local_update(hs["w"], hs["g"], hs["u"], oh["local_lr"], oh["weight_decay"], worker=W - 1)
+    assert compare(st, hs, label="local(W-1)")[0] == 0
+    # warm-up step
+    eng.ssgd_step(hy)
+    oracle.ssgd_step(hs["w"], hs["v"], hs["g"], hs["u"], oh["lr"], oh["momentum"],
+                     oh["weight_decay"], oh["grad_scale"])
+    assert compare(st, hs, label="ssgd")[0] == 0
+    assert eng.iteration == 4
+    assert arenas_intact(arenas)
+    eng.close()
+
+
+@pytest.mark.parametrize("shifts", [{"w": 1}, {"g": 2}, {"u": 3}, {"w": 1, "v": 1, "g": 1, "u": 1}])
+def test_pointers_only_4_byte_aligned_take_the_scalar_path(shifts):
+    say("shifts=%s" % shifts)
+    W = 4
+    st, arenas, gen = custom_state(RAGGED, W, seed=7, shifts=shifts)
+    assert any(t.data_ptr() % 16 for t in st["w"] + st["v"] + st["g"][0] + st["u"][0] if t.numel())
+    hs = host_state(st)
+    eng = make_engine(st)
+    hy = (0.05, 0.02, 0.9, 1e-3, 0.0)
+    oh = oracle_hyper(hy)
+    for _ in range(2):
+        eng.step(hy)
+        oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], **oh)
+        assert compare(st, hs)[0] == 0
+        regen_grads(st, gen)
+        refresh_host_grads(st, hs)
+    eng.local_update(-1, hy)
+    eng.global_update(hy)
+    oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], **oh)
+    assert compare(st, hs)[0] == 0
+    assert arenas_intact(arenas)
+    eng.close()
+
+
+@pytest.mark.parametrize("env", [{"ODSGD_CHUNK_ELEMS": "1024"}, {"ODSGD_CHUNK_ELEMS": "65536"},
+                                 {"ODSGD_BLOCKS_PER_CU": "1"}, {"ODSGD_BLOCKS_PER_CU": "8"},
+                                 {"ODSGD_CHUNK_ELEMS": "2048", "ODSGD_BLOCKS_PER_CU": "2"}])
+def test_launch_shape_does_not_change_results(env):
+    """Chunk size and grid size are tuning only: outputs are bitwise the same."""
+    say("env=%s" % env)
+    sizes = RAGGED + [300000]
+    W = 8
+    old = {k: os.environ.get(k) for k in env}
+    os.environ.update(env)
+    try:
+        st, arenas, gen = custom_state(sizes, W, seed=11)
+        hs = host_state(st)
+        eng = make_engine(st)
+    finally:
+        for k, v in old.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
+    hy = (0.05, 0.02, 0.9, 1e-3, 0.0)
+    oh = oracle_hyper(hy)
+    for _ in range(3):
+        eng.step(hy)
+        oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], **oh)
+        assert compare(st, hs)[0] == 0
+        regen_grads(st, gen)
+        refresh_host_grads(st, hs)
+    assert arenas_intact(arenas)
+    eng.close()
+
+
+# ---------------------------------------------------------------------------
+# special values, resume, error paths with real device memory
+# ---------------------------------------------------------------------------
+def test_special_values_on_gpu():
+    sub = np.float32(1e-41)
+    W = 2
+    wv = np.array([1.0, -0.0, 0.5, 2.0, sub, 3.0, 0.0, 1.0], np.float32)
+    g0 = np.array([0.0, 0.0, np.nan, 1.0, 0.0, np.inf, 2.0 ** -120, -0.0], np.float32)
+    g1 = np.array([0.0, -0.0, 1.0, 1.0, 0.0, 1.0, 2.0 ** -120, -0.0], np.float32)
+    st = {"w": [torch.tensor(wv, device=DEV)], "v": [torch.zeros(8, device=DEV)],
+          "g": [[torch.tensor(g0, device=DEV)], [torch.tensor(g1, device=DEV)]],
+          "u": [[torch.zeros(8, device=DEV)], [torch.zeros(8, device=DEV)]]}
+    hs = host_state(st)
+    eng = make_engine(st)
+    for hy in ((0.5, 0.5, 0.0, 0.0, 0.0), (2.0 ** -20, 2.0 ** -20, 0.5, 0.25, 1.0)):
+        eng.step(hy)
+        oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], **oracle_hyper(hy))
+        torch.cuda.synchronize()
+        for a, b in ((st["w"][0], hs["w"][0]), (st["v"][0], hs["v"][0]),
+                     (st["u"][0][0], hs["u"][0][0]), (st["u"][1][0], hs["u"][1][0])):
+            assert same_bits(a.cpu().numpy(), b), (a.cpu().numpy(), b)
+    # subnormal results were produced and kept (not flushed to zero)
+    assert hs["u"][0][0][4] != 0.0 and abs(hs["u"][0][0][4]) < 1.2e-38
+    eng.close()
+
+
+def test_resume_from_caller_owned_state():
+    """All state lives in the caller's buffers: 6 steps == 3 steps, destroy, re-init, 3 steps."""
+    sizes = [5000, 17]
+    W = 4
+    hy = (0.05, 0.02, 0.9, 1e-3, 0.0)
+    results = []
+    for split_at in (None, 3):
+        st, _, gen = custom_state(sizes, W, seed=21)
+        eng = make_engine(st, warmup_steps=2)
+        for it in range(6):
+            if split_at is not None and it == split_at:
+                eng.close()
+                eng = make_engine(st, warmup_steps=2)
+                B.odsgd_set_iteration(eng.handle, it)
+            eng.step(hy)
+            regen_grads(st, gen)
+        torch.cuda.synchronize()
+        results.append(host_state(st))
+        eng.close()
+    for key in ("w", "v"):
+        for a, b in zip(results[0][key], results[1][key]):
+            assert same_bits(a, b)
+    for m in range(W):
+        for a, b in zip(results[0]["u"][m], results[1]["u"][m]):
+            assert same_bits(a, b)
+
+
+def test_error_paths_with_device_memory():
+    n = 1024
+    t = lambda: torch.zeros(n, device=DEV)
+    w, v, g, u = [t()], [t()], [[t()], [t()]], [[t()], [t()]]
+    nbytes = B.odsgd_workspace_bytes([n], 2)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    ptr = lambda lst: [x.data_ptr() for x in lst]
+
+    def init(**kw):
+        args = dict(numel=[n], w_ptrs=ptr(w), mom_ptrs=ptr(v), grad_ptrs=[ptr(r) for r in g],
+                    local_ptrs=[ptr(r) for r in u], num_workers=2, workspace_ptr=ws.data_ptr(),
+                    workspace_bytes=nbytes, stream=torch.cuda.current_stream().cuda_stream)
+        args.update(kw)
+        return B.odsgd_init(**args)
+
+    for code, kw in ((B.ODSGD_ENOSPC, dict(workspace_bytes=nbytes - 1)),
+                     (B.ODSGD_EALIAS, dict(local_ptrs=[ptr(w), ptr(u[1])])),
+                     (B.ODSGD_EALIAS, dict(local_ptrs=[ptr(u[0]), ptr(u[0])])),
+                     (B.ODSGD_EALIAS, dict(grad_ptrs=[ptr(v), ptr(g[1])])),
+                     (B.ODSGD_EALIGN, dict(mom_ptrs=[v[0].data_ptr() + 2])),
+                     (B.ODSGD_EINVAL, dict(w_ptrs=[0]))):
+        with pytest.raises(B.OdsgdError) as e:
+            init(**kw)
+        assert e.value.code == code, kw
+    # the same gradient buffer registered for both workers is legal
+    h = init(grad_ptrs=[ptr(g[0]), ptr(g[0])])
+    hy = B.odsgd_hyper(0.1, 0.1, 0.9, 0.0, 0.0)
+    import ctypes
+    L = B.lib()
+    s = torch.cuda.current_stream().cuda_stream
+    assert L.odsgd_local_update(h, 2, ctypes.byref(hy), s) == B.ODSGD_EINVAL
+    assert L.odsgd_local_update(h, -2, ctypes.byref(hy), s) == B.ODSGD_EINVAL
+    assert L.odsgd_step(h, None, s) == B.ODSGD_EINVAL
+    assert L.odsgd_set_warmup(h, -1) == B.ODSGD_EINVAL
+    assert B.odsgd_get_iteration(h) == 0
+    B.odsgd_step(h, hy)
+    torch.cuda.synchronize()
+    assert B.odsgd_get_iteration(h) == 1
+    B.odsgd_destroy(h)
+
+
+def test_all_tensors_empty_is_a_no_op():
+    z = lambda: torch.zeros(0, device=DEV)
+    st = {"w": [z()], "v": [z()], "g": [[z()]], "u": [[z()]]}
+    eng = make_engine(st)
+    eng.step((0.1, 0.1, 0.9, 0.0, 0.0))
+    torch.cuda.synchronize()
+    assert eng.iteration == 1
+    eng.close()
+
+
+def test_non_default_stream():
+    sizes = [10000, 33]
+    W = 4
+    st, arenas, gen = custom_state(sizes, W, seed=31)
+    hs = host_state(st)
+    eng = make_engine(st)
+    hy = (0.05, 0.02, 0.9, 1e-3, 0.0)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        eng.step(hy)
+    eng.step(hy, stream=s)
+    s.synchronize()
+    for _ in range(2):
+        oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], **oracle_hyper(hy))
+    assert compare(st, hs)[0] == 0
+    eng.close()
