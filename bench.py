@@ -70,6 +70,26 @@ def time_gpu(wl_mod, B, torch, name, steps, warmup):
     }, st
 
 
+def time_copy_probe(B, torch, steps, warmup, gib=1.0):
+    """Plain copy of `gib` GiB (read) + `gib` GiB (write) per launch, same tile shape as the update kernel."""
+    n = int(gib * (1 << 30)) // 4
+    src = torch.empty(n, dtype=torch.float32, device="cuda:0").normal_()
+    dst = torch.empty_like(src)
+    stream = torch.cuda.current_stream()
+    for _ in range(warmup):
+        B.odsgd_probe_copy(dst, src, stream)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    torch.cuda.synchronize()
+    ev[0].record(stream)
+    for _ in range(steps):
+        B.odsgd_probe_copy(dst, src, stream)
+    ev[1].record(stream)
+    torch.cuda.synchronize()
+    ms = ev[0].elapsed_time(ev[1]) / steps
+    assert torch.equal(dst, src)
+    return {"bytes_per_launch": 8 * n, "kernel_ms_mean": ms, "gbps": 8 * n / (ms * 1e-3) / 1e9}
+
+
 def summarize(r):
     out = dict(r)
     out["params_per_s"] = r["params"] / (r["ms_per_step"] * 1e-3)
@@ -114,6 +134,8 @@ def main():
     ap.add_argument("--others", default="vgg16,alexnet",
                     help="comma list of further workloads measured in the same run ('' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="run only the plain copy kernel of known traffic (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the W workers are W gradient buffers in "
@@ -125,6 +147,12 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     B.lib()  # fail loudly if the extension is missing
+
+    if args.copy_probe:
+        r = time_copy_probe(B, torch, args.steps, args.warmup)
+        r["frac_of_peak"] = r["gbps"] / HBM_PEAK_GBPS
+        print(json.dumps({"copy_probe": r}))
+        return
 
     main_r, st = time_gpu(wl_mod, B, torch, args.workload, args.steps, args.warmup)
     main_s = summarize(main_r)
@@ -143,6 +171,7 @@ def main():
         others[name] = {k: s[k] for k in ("params", "workers", "ms_per_step", "kernel_ms_mean",
                                           "params_per_s", "hbm_gbps", "hbm_frac")}
 
+    probe = time_copy_probe(B, torch, 20, 3)
     w = wl_mod.WORKLOADS[args.workload]
     line = {
         "metric": "params updated/sec per OD-SGD step (and achieved HBM GB/s, see roofline)",
@@ -164,7 +193,9 @@ def main():
                      "unit": "GB/s", "frac": main_s["hbm_frac"],
                      "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
                      "algorithmic_bytes_per_launch": main_s["bytes_per_step"],
-                     "kernel_ms_mean": main_s["kernel_ms_mean"], "kernel_ms_min": main_s["kernel_ms_min"]},
+                     "kernel_ms_mean": main_s["kernel_ms_mean"], "kernel_ms_min": main_s["kernel_ms_min"],
+                     "plain_copy_gbps_same_box": probe["gbps"],
+                     "frac_of_plain_copy": main_s["hbm_gbps"] / probe["gbps"]},
         "cpu_baseline": cpu,
         "other_workloads": others,
         "paper_context": PAPER_CONTEXT,

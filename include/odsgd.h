@@ -151,6 +151,15 @@ int odsgd_set_warmup(odsgd_handle *h, int64_t warmup_steps);
 int64_t odsgd_get_iteration(const odsgd_handle *h);
 int odsgd_set_iteration(odsgd_handle *h, int64_t iteration);
 
+/*
+ * Measurement aid, not part of the method: copy numel floats from src to dst
+ * (both device, 16-byte aligned, numel a multiple of 4, ranges disjoint) with
+ * the same 128-bit streaming accesses the update kernels use.  Its traffic is
+ * known exactly (4*numel bytes read, 4*numel written), which makes it the
+ * yardstick for hardware byte counters and for the copy bandwidth of the box.
+ */
+int odsgd_probe_copy(float *dst, const float *src, size_t numel, void *stream);
+
 /* Release the handle.  Does not touch device memory and does not synchronise:
  * the caller must not free the workspace while enqueued kernels may still run. */
 int odsgd_destroy(odsgd_handle *h);

@@ -68,6 +68,8 @@ def lib():
     L.odsgd_get_iteration.argtypes = [vp]
     L.odsgd_set_iteration.restype = ctypes.c_int
     L.odsgd_set_iteration.argtypes = [vp, ctypes.c_int64]
+    L.odsgd_probe_copy.restype = ctypes.c_int
+    L.odsgd_probe_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     L.odsgd_destroy.restype = ctypes.c_int
     L.odsgd_destroy.argtypes = [vp]
     L.odsgd_strerror.restype = ctypes.c_char_p
@@ -165,6 +167,13 @@ def odsgd_get_iteration(handle):
 
 def odsgd_set_iteration(handle, iteration):
     _call("odsgd_set_iteration", lib().odsgd_set_iteration(handle, int(iteration)))
+
+
+def odsgd_probe_copy(dst, src, stream=None):
+    """Copy tensor src into dst (contiguous fp32 CUDA tensors of equal size)."""
+    assert dst.numel() == src.numel() and dst.dtype == src.dtype == torch.float32
+    _call("odsgd_probe_copy", lib().odsgd_probe_copy(dst.data_ptr(), src.data_ptr(), src.numel(),
+                                                     _stream(stream)))
 
 
 def odsgd_destroy(handle):

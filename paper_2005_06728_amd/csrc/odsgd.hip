@@ -3,11 +3,22 @@
 // One launch covers every parameter tensor ("multi-tensor apply"): odsgd_init
 // cuts the K tensors into fixed-size chunks and writes, into caller-provided
 // device memory, a chunk table (which tensor, where, how many elements) and a
-// pointer table (2 + 2W device pointers per tensor).  A workgroup takes a chunk,
-// fetches its descriptor and pointers with scalar loads, and streams the chunk
-// with 128-bit loads and stores.  The work is purely element-wise (about half a
-// flop per byte), so the only roofline that matters is HBM bandwidth; there is
-// no data reuse, hence no LDS staging and no matrix-core use.
+// pointer table (2 + 2W device pointers per tensor).  A workgroup is a single
+// wavefront; it takes one chunk, fetches its descriptor and pointers with scalar
+// loads, and streams the chunk with 128-bit loads and stores (by default a chunk
+// is 256 elements: one 16-byte access per lane, 1 KiB per wavefront, per array).
+// The work is purely element-wise (about half a flop per byte), so the only
+// roofline that matters is HBM bandwidth; there is no data reuse, hence no LDS
+// staging and no matrix-core use.
+//
+// Launch shape.  With 2W + 4 concurrent streams (W = 8: 20, W = 16: 36) the
+// memory system delivers the most when few, small requests windows are in
+// flight: measured on MI355X, one-wavefront workgroups taking consecutive
+// 1 KiB tiles in dispatch order, with only about 3-4 wavefronts resident per
+// CU, sustain 6.0-6.3 TB/s, against 5.2-5.4 TB/s for the same kernel at full
+// occupancy or as a persistent grid.  Residency is capped by requesting (and
+// never touching) dynamic LDS, the one launch parameter that limits how many
+// workgroups a CU accepts.
 //
 // Arithmetic (paper: Section 3.1, Algorithms 1 and 2; Section 3.3 Local Updater):
 // see include/odsgd.h.  Every statement in the update_* functions below is one
@@ -31,26 +42,23 @@ namespace {
 // ---------------------------------------------------------------------------
 // compile-time tuning knobs (overridable with -D for sweeps)
 // ---------------------------------------------------------------------------
-#ifndef ODSGD_BLOCK
-#define ODSGD_BLOCK 256  // threads per workgroup (4 wavefronts)
-#endif
 #ifndef ODSGD_NT_GRAD
 #define ODSGD_NT_GRAD 1  // gradients are read once: non-temporal loads
 #endif
 #ifndef ODSGD_NT_LOCAL
 #define ODSGD_NT_LOCAL 1  // local weights are written once: non-temporal stores
 #endif
-#ifndef ODSGD_NT_STATE
-#define ODSGD_NT_STATE 1  // w, momentum: next touched one whole step later
+#ifndef ODSGD_NT_STATE_LD
+#define ODSGD_NT_STATE_LD 1  // w, momentum loads: next touched one whole step later
 #endif
-#ifndef ODSGD_UNROLL_SMALL_W
-#define ODSGD_UNROLL_SMALL_W 2  // 128-bit groups in flight per lane when W <= 4
+#ifndef ODSGD_NT_STATE_ST
+#define ODSGD_NT_STATE_ST 1  // w, momentum stores
 #endif
-#ifndef ODSGD_UNROLL_MID_W
-#define ODSGD_UNROLL_MID_W 2  // ... when 4 < W <= 8
-#endif
-#ifndef ODSGD_UNROLL_BIG_W
-#define ODSGD_UNROLL_BIG_W 1  // ... when W > 8
+#define ODSGD_BLOCK 64  // one wavefront per workgroup
+#ifndef ODSGD_INFLIGHT_MEMOPS_PER_CU
+// target of (resident wavefronts per CU) x (128-bit loads + stores per lane per
+// tile); measured optimum 80-96 for every entry point and worker count tried
+#define ODSGD_INFLIGHT_MEMOPS_PER_CU 88
 #endif
 
 constexpr int kBlock = ODSGD_BLOCK;
@@ -172,9 +180,9 @@ __device__ __forceinline__ void apply_fixed(const Ptrs<W_T, MODE> &p, unsigned i
     T w0[U], v0[U], g[U][W_T];
 #pragma unroll
     for (int j = 0; j < U; ++j) {
-        w0[j] = load<ODSGD_NT_STATE, T>(p.w, i + j * kBlock);
+        w0[j] = load<ODSGD_NT_STATE_LD, T>(p.w, i + j * kBlock);
         if constexpr (need_v)
-            v0[j] = load<ODSGD_NT_STATE, T>(p.v, i + j * kBlock);
+            v0[j] = load<ODSGD_NT_STATE_LD, T>(p.v, i + j * kBlock);
 #pragma unroll
         for (int m = 0; m < W_T; ++m)
             g[j][m] = load<ODSGD_NT_GRAD, T>(p.g[m], i + j * kBlock);
@@ -199,8 +207,8 @@ __device__ __forceinline__ void apply_fixed(const Ptrs<W_T, MODE> &p, unsigned i
             }
         }
         if constexpr (MODE != MODE_LOCAL) {
-            store<ODSGD_NT_STATE, T>(p.v, i + j * kBlock, v1);
-            store<ODSGD_NT_STATE, T>(p.w, i + j * kBlock, w1);
+            store<ODSGD_NT_STATE_ST, T>(p.v, i + j * kBlock, v1);
+            store<ODSGD_NT_STATE_ST, T>(p.w, i + j * kBlock, w1);
         }
     }
 }
@@ -212,7 +220,7 @@ __device__ __forceinline__ void apply_generic(ptr_table_t row, uint64_t byte_off
 {
     const uint64_t pw = row[0] + byte_off;
     const uint64_t pv = row[1] + byte_off;
-    T w0 = load<ODSGD_NT_STATE, T>(pw, i);
+    T w0 = load<ODSGD_NT_STATE_LD, T>(pw, i);
     T r = h.weight_decay * w0;
     T s;
     for (int m = 0; m < wcount; ++m) {
@@ -224,7 +232,7 @@ __device__ __forceinline__ void apply_generic(ptr_table_t row, uint64_t byte_off
         }
     }
     if constexpr (MODE != MODE_LOCAL) {
-        T v0 = load<ODSGD_NT_STATE, T>(pv, i);
+        T v0 = load<ODSGD_NT_STATE_LD, T>(pv, i);
         T w1, v1;
         update_global(w0, v0, s, r, h, w1, v1);
         if constexpr (MODE == MODE_SSGD) {
@@ -232,15 +240,9 @@ __device__ __forceinline__ void apply_generic(ptr_table_t row, uint64_t byte_off
                 store<ODSGD_NT_LOCAL, T>(row[2 + wtot + wfirst + m] + byte_off, i, w1);
             }
         }
-        store<ODSGD_NT_STATE, T>(pv, i, v1);
-        store<ODSGD_NT_STATE, T>(pw, i, w1);
+        store<ODSGD_NT_STATE_ST, T>(pv, i, v1);
+        store<ODSGD_NT_STATE_ST, T>(pw, i, w1);
     }
-}
-
-template <int W_T>
-constexpr int unroll_for()
-{
-    return W_T <= 4 ? ODSGD_UNROLL_SMALL_W : (W_T <= 8 ? ODSGD_UNROLL_MID_W : ODSGD_UNROLL_BIG_W);
 }
 
 // ---------------------------------------------------------------------------
@@ -255,6 +257,10 @@ __global__ void __launch_bounds__(kBlock) odsgd_kernel(KernelArgs a)
     const unsigned tid = threadIdx.x;
     const int stride = 2 + 2 * a.wtot;
 
+    // Workgroup b takes chunk b.  The dispatcher hands consecutive workgroups to
+    // the 8 XCDs in turn, so at any moment the chip works on one narrow, sliding
+    // window of each array; giving every XCD a contiguous range of its own
+    // instead was measured 15 % slower.
     for (int c = blockIdx.x; c < a.nchunks; c += gridDim.x) {
         const u4 d = chunks[c];
         const uint32_t tensor = d.x & ~kVecFlag;
@@ -273,13 +279,7 @@ __global__ void __launch_bounds__(kBlock) odsgd_kernel(KernelArgs a)
                 p.g[m] = row[2 + a.wfirst + m] + byte_off;
                 p.u[m] = row[2 + a.wtot + a.wfirst + m] + byte_off;
             }
-            constexpr int U = unroll_for<W_T>();
-            unsigned i = tid;
-            if constexpr (U > 1) {
-                for (; i + (U - 1) * kBlock < nvec; i += U * kBlock)
-                    apply_fixed<W_T, MODE, U, f4>(p, i, h);
-            }
-            for (; i < nvec; i += kBlock)
+            for (unsigned i = tid; i < nvec; i += kBlock)
                 apply_fixed<W_T, MODE, 1, f4>(p, i, h);
             for (unsigned t = nvec * 4 + tid; t < count; t += kBlock)
                 apply_fixed<W_T, MODE, 1, float>(p, t, h);
@@ -292,6 +292,18 @@ __global__ void __launch_bounds__(kBlock) odsgd_kernel(KernelArgs a)
     }
 }
 
+// Plain copy, one 1 KiB tile per wavefront: a kernel of exactly known traffic
+// (n*4 bytes read, n*4 bytes written) for calibrating HBM byte counters.
+__global__ void __launch_bounds__(kBlock) odsgd_probe_copy_kernel(uint64_t dst, uint64_t src, uint64_t nvec)
+{
+    const uint64_t tile = blockIdx.x;
+    const uint64_t i = tile * kBlock + threadIdx.x;
+    if (i < nvec) {
+        const f4 x = load<true, f4>(src + tile * (kBlock * sizeof(f4)), threadIdx.x);
+        store<true, f4>(dst + tile * (kBlock * sizeof(f4)), threadIdx.x, x);
+    }
+}
+
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
@@ -300,6 +312,7 @@ thread_local hipError_t g_last_hip_error = hipSuccess;
 struct Tuning {
     int64_t chunk_elems;  // elements per chunk (multiple of 4 * kBlock)
     int blocks_per_cu;    // grid cap = blocks_per_cu * CUs; 0 = one workgroup per chunk
+    int waves_per_cu;     // resident wavefronts per CU: 0 = choose per launch, < 0 = no cap
 };
 
 int64_t env_int(const char *name, int64_t dflt)
@@ -315,7 +328,7 @@ int64_t env_int(const char *name, int64_t dflt)
 Tuning current_tuning()
 {
     Tuning t;
-    t.chunk_elems = env_int("ODSGD_CHUNK_ELEMS", 4096);
+    t.chunk_elems = env_int("ODSGD_CHUNK_ELEMS", 4 * kBlock);
     const int64_t q = 4 * kBlock;
     if (t.chunk_elems < q)
         t.chunk_elems = q;
@@ -325,6 +338,7 @@ Tuning current_tuning()
     t.blocks_per_cu = (int)env_int("ODSGD_BLOCKS_PER_CU", 0);
     if (t.blocks_per_cu < 0)
         t.blocks_per_cu = 0;
+    t.waves_per_cu = (int)env_int("ODSGD_WAVES_PER_CU", 0);
     return t;
 }
 
@@ -418,6 +432,7 @@ struct odsgd_handle {
     const void *d_ptrs;
     int device;
     int num_cus;
+    int lds_per_cu;
     Tuning tuning;
     int64_t iteration;
     int64_t warmup_steps;
@@ -425,6 +440,37 @@ struct odsgd_handle {
 };
 
 namespace {
+
+// Dynamic LDS to request so that a CU holds about `waves` one-wavefront
+// workgroups.  The kernels never touch LDS; the request only limits residency.
+// LDS is handed out in 1280-byte granules; a workgroup may ask for at most 64 KiB
+// (so two resident wavefronts per CU is the lowest cap).
+size_t occupancy_cap_lds_bytes(const odsgd_handle *h, int mode, int wcount)
+{
+    int waves = h->tuning.waves_per_cu;
+    if (waves < 0)
+        return 0;
+    if (waves == 0) {
+        // memory instructions (loads + stores) one lane issues per tile
+        const int loads = (mode == MODE_LOCAL) ? wcount + 1 : wcount + 2;
+        const int stores = (mode == MODE_GLOBAL) ? 2 : (mode == MODE_LOCAL) ? wcount : wcount + 2;
+        const int ops = loads + stores;
+        // nearest integer; rounded up once a tile spans many arrays
+        waves = (ops < 24) ? (ODSGD_INFLIGHT_MEMOPS_PER_CU + ops / 2) / ops
+                           : (ODSGD_INFLIGHT_MEMOPS_PER_CU + ops - 1) / ops;
+        if (waves > 16)
+            return 0;  // few streams: full occupancy is best
+    }
+    if (waves < 2)
+        waves = 2;
+    const size_t granule = 1280;
+    size_t bytes = (size_t)h->lds_per_cu / (size_t)waves / granule * granule;
+    if (bytes > 65536)
+        bytes = 65536;
+    if (bytes < granule)
+        return 0;  // more wavefronts than the cap can express: no cap
+    return bytes;
+}
 
 int launch(odsgd_handle *h, int mode, int wfirst, int wcount, const odsgd_hyper *hy, void *stream)
 {
@@ -447,7 +493,8 @@ int launch(odsgd_handle *h, int mode, int wfirst, int wcount, const odsgd_hyper 
     if (h->tuning.blocks_per_cu > 0)
         grid = std::min<int64_t>(grid, (int64_t)h->tuning.blocks_per_cu * h->num_cus);
     KernelFn fn = pick_kernel(mode, wcount);
-    hipLaunchKernelGGL(fn, dim3((unsigned)grid), dim3(kBlock), 0, (hipStream_t)stream, a);
+    const size_t lds = occupancy_cap_lds_bytes(h, mode, wcount);
+    hipLaunchKernelGGL(fn, dim3((unsigned)grid), dim3(kBlock), lds, (hipStream_t)stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         g_last_hip_error = e;
@@ -546,6 +593,11 @@ int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel, float 
         int cus = 0;
         e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device);
         h->num_cus = cus > 0 ? cus : 256;
+    }
+    if (e == hipSuccess) {
+        int lds = 0;
+        e = hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, h->device);
+        h->lds_per_cu = lds > 0 ? lds : 160 * 1024;
     }
     if (e != hipSuccess) {
         g_last_hip_error = e;
@@ -658,6 +710,26 @@ int odsgd_set_iteration(odsgd_handle *h, int64_t iteration)
     if (!h || iteration < 0)
         return ODSGD_EINVAL;
     h->iteration = iteration;
+    return ODSGD_OK;
+}
+
+int odsgd_probe_copy(float *dst, const float *src, size_t numel, void *stream)
+{
+    if (!dst || !src || numel % 4 != 0 || (uintptr_t)dst % 16 != 0 || (uintptr_t)src % 16 != 0)
+        return ODSGD_EINVAL;
+    const uint64_t nvec = numel / 4;
+    const uint64_t tiles = (nvec + kBlock - 1) / kBlock;
+    if (tiles > (uint64_t)kMaxChunks)
+        return ODSGD_ERANGE;
+    if (tiles == 0)
+        return ODSGD_OK;
+    hipLaunchKernelGGL(odsgd_probe_copy_kernel, dim3((unsigned)tiles), dim3(kBlock), 0, (hipStream_t)stream,
+                       (uint64_t)(uintptr_t)dst, (uint64_t)(uintptr_t)src, nvec);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        g_last_hip_error = e;
+        return ODSGD_EHIP;
+    }
     return ODSGD_OK;
 }
 

@@ -181,15 +181,40 @@ def fill_grads_(bufs, wl, iteration, worker):
             buf.masked_fill_(mask, 0.0)
 
 
-def allocate(wl, device, num_workers=None):
+def _arena_views(ns, streams, device, skew_bytes):
+    """One allocation holding `streams` flat buckets.  Inside a bucket the K
+    tensors are packed at 16-byte aligned offsets; bucket j starts at
+    j * (bucket size rounded up to 2 MiB + skew_bytes), so that equal element
+    offsets in different buckets do not share their low address bits."""
+    offs, o = [], 0
+    for n in ns:
+        offs.append(o)
+        o += (n + 3) // 4 * 4
+    bucket = (o * 4 + (1 << 21) - 1) // (1 << 21) * (1 << 21) + skew_bytes
+    assert bucket % 16 == 0
+    arena = torch.empty(bucket * streams // 4, dtype=torch.float32, device=device)
+    views = [[arena[j * (bucket // 4) + a: j * (bucket // 4) + a + n] for a, n in zip(offs, ns)]
+             for j in range(streams)]
+    return arena, views
+
+
+def allocate(wl, device, num_workers=None, layout="separate", skew_bytes=12288):
     """Allocate the full resident state for a workload: one flat fp32 tensor per
     parameter tensor per role.  Returns dict(w, v, g, u) with w, v: [K] and
     g, u: [W][K].  Momentum is zero, local weights start as a copy of w_0
-    (workers pull the initial weights before the first iteration, Alg. 2)."""
+    (workers pull the initial weights before the first iteration, Alg. 2).
+
+    layout="separate": every tensor is its own torch allocation.
+    layout="arena":    2 + 2W flat buckets (w, v, g_0.., u_0..) in one allocation,
+                       consecutive buckets staggered by skew_bytes."""
     W = wl.num_workers if num_workers is None else num_workers
     ns = numels(wl)
-    mk = lambda: [torch.empty(n, dtype=torch.float32, device=device) for n in ns]
-    st = {"w": mk(), "v": mk(), "g": [mk() for _ in range(W)], "u": [mk() for _ in range(W)]}
+    if layout == "arena":
+        arena, views = _arena_views(ns, 2 + 2 * W, device, skew_bytes)
+        st = {"w": views[0], "v": views[1], "g": views[2:2 + W], "u": views[2 + W:], "arena": arena}
+    else:
+        mk = lambda: [torch.empty(n, dtype=torch.float32, device=device) for n in ns]
+        st = {"w": mk(), "v": mk(), "g": [mk() for _ in range(W)], "u": [mk() for _ in range(W)]}
     fill_weights_(st["w"], wl)
     for b in st["v"]:
         b.zero_()

@@ -74,7 +74,7 @@ def regen_grads(st, gen, gstd=1e-3):
             t.normal_(0, gstd, generator=gen)
 
 
-RAGGED = [0, 1, 3, 4, 5, 1023, 1024, 1025, 4096, 4097, 8191, 3 * 4096 + 7, 20000]
+RAGGED = [0, 1, 3, 4, 5, 255, 256, 257, 1023, 1024, 1025, 4096, 4097, 8191, 3 * 4096 + 7, 20000]
 
 
 # ---------------------------------------------------------------------------
@@ -106,11 +106,11 @@ def test_hand_expanded_sequence_on_gpu(golden_w2):
 # ---------------------------------------------------------------------------
 # the five parameter sets, fused step, all outputs compared after every iteration
 # ---------------------------------------------------------------------------
-def run_workload(name, iterations, warmup=0):
+def run_workload(name, iterations, warmup=0, layout="separate"):
     w = wl.WORKLOADS[name]
     say("workload %s: K=%d N=%d W=%d iterations=%d warmup=%d" %
         (name, len(w.tensors), wl.total_params(w), w.num_workers, iterations, warmup))
-    st = wl.allocate(w, DEV)
+    st = wl.allocate(w, DEV, layout=layout)
     hs = host_state(st)
     eng = make_engine(st, warmup_steps=warmup)
     hy = hyper_tuple(w.hyper)
@@ -150,6 +150,26 @@ def test_vgg16_full_size_with_exact_zero_gradients():
 
 def test_resnet20_with_warmup_schedule():
     assert run_workload("resnet20", 8, warmup=3) == 0
+
+
+def test_lenet5_packed_buckets_layout():
+    """All tensors of a role packed back to back in one flat bucket (the usual
+    gradient-bucket layout): neighbours are other tensors, not padding."""
+    assert run_workload("lenet5", 4, layout="arena") == 0
+
+
+def test_probe_copy():
+    src = torch.randn(1 << 20, device=DEV)
+    dst = torch.zeros_like(src)
+    B.odsgd_probe_copy(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    a, b = torch.randn(1000, device=DEV), torch.zeros(1000, device=DEV)
+    B.odsgd_probe_copy(b[:996], a[:996])
+    torch.cuda.synchronize()
+    assert torch.equal(b[:996], a[:996]) and torch.all(b[996:] == 0)
+    with pytest.raises(B.OdsgdError):
+        B.odsgd_probe_copy(b[:998], a[:998])  # not a multiple of 4
 
 
 # ---------------------------------------------------------------------------
@@ -224,7 +244,9 @@ def test_pointers_only_4_byte_aligned_take_the_scalar_path(shifts):
 
 @pytest.mark.parametrize("env", [{"ODSGD_CHUNK_ELEMS": "1024"}, {"ODSGD_CHUNK_ELEMS": "65536"},
                                  {"ODSGD_BLOCKS_PER_CU": "1"}, {"ODSGD_BLOCKS_PER_CU": "8"},
-                                 {"ODSGD_CHUNK_ELEMS": "2048", "ODSGD_BLOCKS_PER_CU": "2"}])
+                                 {"ODSGD_CHUNK_ELEMS": "2048", "ODSGD_BLOCKS_PER_CU": "2"},
+                                 {"ODSGD_WAVES_PER_CU": "-1"}, {"ODSGD_WAVES_PER_CU": "2"},
+                                 {"ODSGD_WAVES_PER_CU": "7", "ODSGD_CHUNK_ELEMS": "512"}])
 def test_launch_shape_does_not_change_results(env):
     """Chunk size and grid size are tuning only: outputs are bitwise the same."""
     say("env=%s" % env)
