@@ -25,7 +25,7 @@ HBM_PEAK_GBPS = 8000.0
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs,
 # scaled by the same counters on the 1 GiB copy probe); see profiles/.  Absent = not measured.
-MEASURED_TRAFFIC_BYTES = {"resnet50": 2.0578e9}
+MEASURED_TRAFFIC_BYTES = {"resnet50": 2.0578e9, "vgg16": 1.9996e10}
 
 PAPER_CONTEXT = {
     "note": "the paper reports end-to-end training speed only, never the update path; other hardware, context only",
