@@ -21,13 +21,13 @@ def build(force=False, extra_cflags=(), lib=LIB, src=SRC):
             and os.path.getmtime(lib) >= os.path.getmtime(src)):
         return lib
     objs = []
-    for real, suffix in (("float", "f32"), ("double", "f64")):
+    for real, suffix, sqrt in (("float", "f32", "sqrtf"), ("double", "f64", "sqrt")):
         obj = lib + "." + suffix + ".o"
         cmd = ["gcc", *CFLAGS, *extra_cflags, "-DODSGD_REAL=" + real,
-               "-DODSGD_SUFFIX=" + suffix, "-c", src, "-o", obj]
+               "-DODSGD_SUFFIX=" + suffix, "-DODSGD_SQRT=" + sqrt, "-c", src, "-o", obj]
         subprocess.run(cmd, check=True)
         objs.append(obj)
-    subprocess.run(["gcc", "-shared", "-o", lib, *objs, *extra_cflags], check=True)
+    subprocess.run(["gcc", "-shared", "-o", lib, *objs, *extra_cflags, "-lm"], check=True)
     for o in objs:
         os.remove(o)
     return lib

@@ -39,11 +39,24 @@
  *
  * Layout: one call handles ONE parameter tensor, given as flat arrays of n
  * elements; g and u are arrays of M pointers (one per worker).
+ *
+ * Delay-compensated local updaters (Section 3.3, equations "DC-ASGD-c" and
+ * "DC-ASGD-a" with the MeanSquare recurrence).  The equations are printed for
+ * asynchronous SGD; inside OD-SGD their symbols are read as
+ *     w_{t+tau}   = the freshly copied global weights w_t the update starts from
+ *     w_t         = the weights the gradient g_m was evaluated at, i.e. worker
+ *                   m's previous local weights (the old content of u[m])
+ *     g(w_t)      = g_m,   eta = local_lr
+ * and weight decay enters as in the SGD updater (r = wd * w added to the
+ * gradient term only; the compensation term uses the raw gradient, so wd = 0
+ * gives the printed equation).  Products are taken left to right as
+ * ((g*g) * (w - u_old)) * lambda.
  */
+#include <math.h>
 #include <stdint.h>
 
-#ifndef ODSGD_REAL
-#error "compile with -DODSGD_REAL=float|double -DODSGD_SUFFIX=f32|f64"
+#if !defined(ODSGD_REAL) || !defined(ODSGD_SUFFIX) || !defined(ODSGD_SQRT)
+#error "compile with -DODSGD_REAL=float|double -DODSGD_SUFFIX=f32|f64 -DODSGD_SQRT=sqrtf|sqrt"
 #endif
 #define ODSGD_CAT2(a, b) a##_##b
 #define ODSGD_CAT(a, b) ODSGD_CAT2(a, b)
@@ -76,6 +89,75 @@ void ODSGD_NAME(odsgd_oracle_local)(int64_t n, int M, const real *w,
                 continue;
             real dm = g[m][i] + r;
             real pm = local_lr * dm;
+            u[m][i] = w0 - pm;
+        }
+    }
+}
+
+/*
+ * Local update with the constant delay compensation of equation "DC-ASGD-c":
+ *   u_m <- w - local_lr * ( (g_m + r) + lambda * g_m*g_m*(w - u_m_old) ).
+ * u[m] is read (old local weights) and then overwritten.
+ */
+void ODSGD_NAME(odsgd_oracle_local_dcasgd_c)(int64_t n, int M, const real *w,
+                                             const real *const *g, real *const *u,
+                                             int worker, real local_lr,
+                                             real weight_decay, real lambda)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        real w0 = w[i];
+        real r = weight_decay * w0;
+        for (int m = 0; m < M; ++m) {
+            if (worker >= 0 && m != worker)
+                continue;
+            real gm = g[m][i];
+            real dlt = w0 - u[m][i];
+            real gg = gm * gm;
+            real c1 = gg * dlt;
+            real c2 = c1 * lambda;
+            real dm = gm + r;
+            real em = dm + c2;
+            real pm = local_lr * em;
+            u[m][i] = w0 - pm;
+        }
+    }
+}
+
+/*
+ * Local update with the adaptive compensation of equation "DC-ASGD-a":
+ *   MeanSquare <- ms_decay * MeanSquare + (1 - ms_decay) * g_m*g_m   (per worker state)
+ *   lambda_eff  = lambda / sqrt(MeanSquare + epsilon)
+ *   u_m <- w - local_lr * ( (g_m + r) + lambda_eff * g_m*g_m*(w - u_m_old) ).
+ */
+void ODSGD_NAME(odsgd_oracle_local_dcasgd_a)(int64_t n, int M, const real *w,
+                                             const real *const *g, real *const *u,
+                                             real *const *ms, int worker,
+                                             real local_lr, real weight_decay,
+                                             real lambda, real ms_decay,
+                                             real epsilon)
+{
+    real one_minus_decay = (real)1 - ms_decay;
+    for (int64_t i = 0; i < n; ++i) {
+        real w0 = w[i];
+        real r = weight_decay * w0;
+        for (int m = 0; m < M; ++m) {
+            if (worker >= 0 && m != worker)
+                continue;
+            real gm = g[m][i];
+            real dlt = w0 - u[m][i];
+            real gg = gm * gm;
+            real s1 = ms_decay * ms[m][i];
+            real s2 = one_minus_decay * gg;
+            real msq = s1 + s2;
+            ms[m][i] = msq;
+            real rad = msq + epsilon;
+            real den = ODSGD_SQRT(rad);
+            real lam = lambda / den;
+            real c1 = gg * dlt;
+            real c2 = c1 * lam;
+            real dm = gm + r;
+            real em = dm + c2;
+            real pm = local_lr * em;
             u[m][i] = w0 - pm;
         }
     }

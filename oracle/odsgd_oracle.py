@@ -60,6 +60,42 @@ def local_update(w, g, u, local_lr, weight_decay, worker=-1):
            ct(local_lr), ct(weight_decay))
 
 
+def local_update_dcasgd_c(w, g, u, local_lr, weight_decay, lam, worker=-1):
+    """Local update, constant delay compensation. u[m] holds the weights the
+    gradient was taken at on entry and the new local weights on return."""
+    M = len(g)
+    for k in range(len(w)):
+        dt = w[k].dtype
+        ct, sfx = _CT[dt]
+        n = w[k].shape[0]
+        gk = [g[m][k] for m in range(M)]
+        uk = [u[m][k] for m in range(M)]
+        _check([w[k]] + gk + uk, dt, n)
+        fn = getattr(lib(), "odsgd_oracle_local_dcasgd_c_" + sfx)
+        fn.restype = None
+        fn(ctypes.c_int64(n), ctypes.c_int(M), w[k].ctypes.data_as(ctypes.POINTER(ct)),
+           _ptr_array(gk, ct), _ptr_array(uk, ct), ctypes.c_int(worker),
+           ct(local_lr), ct(weight_decay), ct(lam))
+
+
+def local_update_dcasgd_a(w, g, u, ms, local_lr, weight_decay, lam, ms_decay, epsilon, worker=-1):
+    """Local update, adaptive delay compensation; ms[m][k] is the MeanSquare state."""
+    M = len(g)
+    for k in range(len(w)):
+        dt = w[k].dtype
+        ct, sfx = _CT[dt]
+        n = w[k].shape[0]
+        gk = [g[m][k] for m in range(M)]
+        uk = [u[m][k] for m in range(M)]
+        mk = [ms[m][k] for m in range(M)]
+        _check([w[k]] + gk + uk + mk, dt, n)
+        fn = getattr(lib(), "odsgd_oracle_local_dcasgd_a_" + sfx)
+        fn.restype = None
+        fn(ctypes.c_int64(n), ctypes.c_int(M), w[k].ctypes.data_as(ctypes.POINTER(ct)),
+           _ptr_array(gk, ct), _ptr_array(uk, ct), _ptr_array(mk, ct), ctypes.c_int(worker),
+           ct(local_lr), ct(weight_decay), ct(lam), ct(ms_decay), ct(epsilon))
+
+
 def global_update(w, v, g, lr, momentum, weight_decay, grad_scale=0.0):
     """Server-side global update, tensor list form. w, v: [K], g: [M][K]."""
     M = len(g)
@@ -112,10 +148,23 @@ def ssgd_step(w, v, g, u, lr, momentum, weight_decay, grad_scale=0.0):
            ct(weight_decay), ct(grad_scale))
 
 
-def step(i, warmup_steps, w, v, g, u, lr, local_lr, momentum, weight_decay, grad_scale=0.0):
+def step(i, warmup_steps, w, v, g, u, lr, local_lr, momentum, weight_decay, grad_scale=0.0,
+         rule=None):
     """Iteration i of the whole schedule of Alg. 2: synchronous SGD while
-    i < warmup_steps, one-step-delay iteration from i == warmup_steps on."""
+    i < warmup_steps, one-step-delay iteration from i == warmup_steps on.
+
+    rule: None for the SGD local updater, ("dcasgd_c", lam) or
+    ("dcasgd_a", lam, ms_decay, epsilon, ms) for the delay-compensated ones.  By
+    definition the OD iteration is the local update followed by the global one."""
     if i < warmup_steps:
         ssgd_step(w, v, g, u, lr, momentum, weight_decay, grad_scale)
-    else:
+    elif rule is None:
         od_step(w, v, g, u, lr, local_lr, momentum, weight_decay, grad_scale)
+    else:
+        if rule[0] == "dcasgd_c":
+            local_update_dcasgd_c(w, g, u, local_lr, weight_decay, rule[1])
+        elif rule[0] == "dcasgd_a":
+            local_update_dcasgd_a(w, g, u, rule[4], local_lr, weight_decay, rule[1], rule[2], rule[3])
+        else:
+            raise ValueError(rule[0])
+        global_update(w, v, g, lr, momentum, weight_decay, grad_scale)

@@ -26,8 +26,8 @@ def load_golden(name):
         if key == "iter":
             cur = {}
             out["iters"].append(cur)
-        elif key == "hyper":
-            out["hyper"] = {k: float(x) for k, x in (v.split("=") for v in vals)}
+        elif key in ("hyper", "rule_c", "rule_a"):
+            out[key] = {k: float(x) for k, x in (v.split("=") for v in vals)}
         elif key == "tensors":
             out["tensors"] = [int(x) for x in vals]
         else:
@@ -38,3 +38,8 @@ def load_golden(name):
 @pytest.fixture(scope="session")
 def golden_w2():
     return load_golden("hand_expanded_w2.txt")
+
+
+@pytest.fixture(scope="session")
+def golden_dcasgd():
+    return load_golden("hand_expanded_dcasgd.txt")
