@@ -90,7 +90,8 @@ size_t odsgd_workspace_bytes(int num_tensors, const int64_t *numel, int num_work
  *                  worker m's gradient of tensor k, read only.  The buffers are
  *                  registered once; the caller refills them in place each iteration
  *   local_w        host array [W] of host arrays [K] of device pointers:
- *                  worker m's local weights of tensor k, written only
+ *                  worker m's local weights of tensor k; written only with the SGD
+ *                  local updater, read and written with the delay-compensated ones
  *   num_workers    1 <= W <= ODSGD_MAX_WORKERS
  *   workspace      device, >= odsgd_workspace_bytes(...) bytes, 256-byte aligned,
  *                  must stay valid and untouched until odsgd_destroy
@@ -140,6 +141,37 @@ int odsgd_step(odsgd_handle *h, const odsgd_hyper *hyper, void *stream);
  * local_w[m] receives the new global weights.  Advances the iteration counter.
  */
 int odsgd_ssgd_step(odsgd_handle *h, const odsgd_hyper *hyper, void *stream);
+
+/*
+ * Local updater used by odsgd_local_update and by the one-step-delay iterations
+ * of odsgd_step (Section 3.3 "Local Updater": SGD, DC-ASGD-c, DC-ASGD-a).
+ * With u_old = the weights worker m evaluated its gradient at (what local_w[m]
+ * holds on entry) and g = grads[m]:
+ *   ODSGD_LOCAL_SGD       local_w[m] = w - local_lr*((g + r))
+ *   ODSGD_LOCAL_DCASGD_C  local_w[m] = w - local_lr*((g + r) + ((g*g)*(w - u_old))*lambda)
+ *   ODSGD_LOCAL_DCASGD_A  ms[m]      = ms_decay*ms[m] + (1 - ms_decay)*(g*g)
+ *                         local_w[m] = w - local_lr*((g + r) + ((g*g)*(w - u_old))*(lambda/sqrt(ms[m] + epsilon)))
+ * r = weight_decay*w; sqrt and divide are correctly rounded.  For the two
+ * delay-compensated rules local_w[m] is read before it is overwritten, so it
+ * must be initialised (to the weights the first gradients were taken at).
+ * mean_square: host array [W] of host arrays [K] of device pointers to the
+ * per-worker MeanSquare state (numel[k] floats each, 16-byte aligned, read and
+ * written, caller-owned, zero for a fresh run); required for DCASGD_A, ignored
+ * otherwise.  The pointers are uploaded on `stream`; the call returns after the
+ * upload.  The paper gives lambda = 0.04 (c), lambda = 2 with ms_decay 0.95 or 0
+ * (a) and never states epsilon.
+ */
+#define ODSGD_LOCAL_SGD 0
+#define ODSGD_LOCAL_DCASGD_C 1
+#define ODSGD_LOCAL_DCASGD_A 2
+typedef struct {
+    int rule;
+    float lambda;
+    float ms_decay;
+    float epsilon;
+} odsgd_local_rule;
+int odsgd_set_local_rule(odsgd_handle *h, const odsgd_local_rule *rule,
+                         float *const *const *mean_square, void *stream);
 
 /*
  * Warm-up length wp >= 0 (Alg. 2 input): iterations 0..wp-1 are synchronous SGD,

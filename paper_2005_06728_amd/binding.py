@@ -20,12 +20,20 @@ ODSGD_ENOSPC = -4
 ODSGD_EHIP = -5
 ODSGD_ERANGE = -6
 ODSGD_MAX_WORKERS = 64
+ODSGD_LOCAL_SGD = 0
+ODSGD_LOCAL_DCASGD_C = 1
+ODSGD_LOCAL_DCASGD_A = 2
 
 
 class odsgd_hyper(ctypes.Structure):
     _fields_ = [("lr", ctypes.c_float), ("local_lr", ctypes.c_float),
                 ("momentum", ctypes.c_float), ("weight_decay", ctypes.c_float),
                 ("grad_scale", ctypes.c_float)]
+
+
+class odsgd_local_rule(ctypes.Structure):
+    _fields_ = [("rule", ctypes.c_int), ("lambda_", ctypes.c_float),
+                ("ms_decay", ctypes.c_float), ("epsilon", ctypes.c_float)]
 
 
 class OdsgdError(RuntimeError):
@@ -62,6 +70,8 @@ def lib():
         fn = getattr(L, name)
         fn.restype = ctypes.c_int
         fn.argtypes = [vp, hp, vp]
+    L.odsgd_set_local_rule.restype = ctypes.c_int
+    L.odsgd_set_local_rule.argtypes = [vp, ctypes.POINTER(odsgd_local_rule), vp, vp]
     L.odsgd_set_warmup.restype = ctypes.c_int
     L.odsgd_set_warmup.argtypes = [vp, ctypes.c_int64]
     L.odsgd_get_iteration.restype = ctypes.c_int64
@@ -157,6 +167,18 @@ def odsgd_ssgd_step(handle, hyper, stream=None):
           lib().odsgd_ssgd_step(handle, ctypes.byref(_hyper(hyper)), _stream(stream)))
 
 
+def odsgd_set_local_rule(handle, rule, lam=0.0, ms_decay=0.0, epsilon=0.0, mean_square_ptrs=None,
+                         stream=None):
+    """rule: ODSGD_LOCAL_*; mean_square_ptrs: [W][K] integers (DCASGD_A only)."""
+    r = odsgd_local_rule(int(rule), float(lam), float(ms_decay), float(epsilon))
+    top, keep = (None, None) if mean_square_ptrs is None else _ptr_rows(mean_square_ptrs)
+    rc = lib().odsgd_set_local_rule(handle, ctypes.byref(r),
+                                    None if top is None else ctypes.cast(top, ctypes.c_void_p),
+                                    _stream(stream))
+    del keep
+    _call("odsgd_set_local_rule", rc)
+
+
 def odsgd_set_warmup(handle, warmup_steps):
     _call("odsgd_set_warmup", lib().odsgd_set_warmup(handle, int(warmup_steps)))
 
@@ -202,6 +224,12 @@ class Engine:
             W, self.workspace.data_ptr(), nbytes, _stream(stream))
         if warmup_steps:
             odsgd_set_warmup(self.handle, warmup_steps)
+
+    def set_local_rule(self, rule, lam=0.0, ms_decay=0.0, epsilon=0.0, mean_square=None, stream=None):
+        """mean_square: [W][K] fp32 CUDA tensors holding the MeanSquare state (DCASGD_A)."""
+        self.mean_square = mean_square
+        ptrs = None if mean_square is None else [[t.data_ptr() for t in r] for r in mean_square]
+        odsgd_set_local_rule(self.handle, rule, lam, ms_decay, epsilon, ptrs, stream)
 
     def step(self, hyper, stream=None):
         odsgd_step(self.handle, hyper, stream)

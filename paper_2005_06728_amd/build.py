@@ -3,6 +3,7 @@
 hipcc cross-compiles without a GPU.  Flags that matter for results:
   -ffp-contract=off                      no fused multiply-add (each operation rounds once)
   -fno-gpu-flush-denormals-to-zero       binary32 subnormals are kept
+  -fhip-fp32-correctly-rounded-divide-sqrt   IEEE divide and square root
   -Xclang -target-feature -Xclang -packed-fp32-ops   no packed-fp32 instructions
 """
 import os
@@ -17,6 +18,7 @@ LIB = os.path.join(HERE, "libodsgd.so")
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
     "-ffp-contract=off", "-fno-gpu-flush-denormals-to-zero",
+    "-fhip-fp32-correctly-rounded-divide-sqrt",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wextra", "-Wno-unused-parameter",
     "-I", os.path.join(ROOT, "include"),

@@ -92,14 +92,22 @@ enum Mode : int {
     MODE_LOCAL = 3,   // local update only, workers [wfirst, wfirst + wcount)
 };
 
+// local updater applied by MODE_OD / MODE_LOCAL (Section 3.3, "Local Updater")
+enum Rule : int {
+    RULE_SGD = 0,  // u_m = w - local_lr*(g_m + r)
+    RULE_DCC = 1,  // + lambda * g_m*g_m*(w - u_m_old)                         (eq. DC-ASGD-c)
+    RULE_DCA = 2,  // + lambda/sqrt(MeanSquare_m + eps) * g_m*g_m*(w - u_m_old) (eq. DC-ASGD-a)
+};
+
 struct KernelArgs {
     const void *chunks;  // device: nchunks * 16 bytes
-    const void *ptrs;    // device: K rows of (2 + 2*wtot) pointers
+    const void *ptrs;    // device: K rows of (2 + 3*wtot) pointers
     int nchunks;
-    int wtot;    // workers registered (row stride = 2 + 2*wtot)
+    int wtot;    // workers registered (row = [w, v, g_0.., u_0.., ms_0..], stride 2 + 3*wtot)
     int wfirst;  // first worker this launch touches
     int wcount;  // number of workers this launch touches (== W_T when W_T > 0)
     float lr, local_lr, momentum, weight_decay, grad_scale;
+    float lambda, ms_decay, one_minus_ms_decay, epsilon;
 };
 
 // chunk descriptor, 16 bytes: {tensor | vec<<31, count, offset_lo, offset_hi}
@@ -132,19 +140,53 @@ __device__ __forceinline__ void store(uint64_t base, unsigned idx, T x)
 }
 
 // ---------------------------------------------------------------------------
-// the update rules; T is float or f4 (element-wise)
+// the update rules; T is float or f4 (element-wise).  One statement = one
+// binary32 operation (sqrt and divide are the correctly rounded ones).
 // ---------------------------------------------------------------------------
 struct Hyp {
     float lr, local_lr, momentum, weight_decay, grad_scale;
+    float lambda, ms_decay, one_minus_ms_decay, epsilon;
 };
 
-// u_m = w_t - local_lr * (g_m + r)
+__device__ __forceinline__ float sqrt_rn(float x) { return __builtin_sqrtf(x); }
+__device__ __forceinline__ f4 sqrt_rn(f4 x)
+{
+    return f4{__builtin_sqrtf(x.x), __builtin_sqrtf(x.y), __builtin_sqrtf(x.z), __builtin_sqrtf(x.w)};
+}
+
+// SGD local updater: u_m = w_t - local_lr * (g_m + r)
 template <typename T>
 __device__ __forceinline__ T update_local(T w0, T g, T r, float local_lr)
 {
     T dm = g + r;
     T pm = local_lr * dm;
     return w0 - pm;
+}
+
+// delay-compensated local updaters; u_old = the weights g was evaluated at.
+// lam is the scalar lambda (RULE_DCC) or the per-element lambda/sqrt(ms+eps) (RULE_DCA).
+template <typename T, typename L>
+__device__ __forceinline__ T update_local_dc(T w0, T g, T gg, T u_old, T r, L lam, float local_lr)
+{
+    T dlt = w0 - u_old;
+    T c1 = gg * dlt;
+    T c2 = c1 * lam;
+    T dm = g + r;
+    T em = dm + c2;
+    T pm = local_lr * em;
+    return w0 - pm;
+}
+
+// MeanSquare_m <- ms_decay * MeanSquare_m + (1 - ms_decay) * g*g; returns lambda / sqrt(ms + eps)
+template <typename T>
+__device__ __forceinline__ T mean_square_step(T gg, T ms_old, const Hyp &h, T &ms_new)
+{
+    T s1 = h.ms_decay * ms_old;
+    T s2 = h.one_minus_ms_decay * gg;
+    ms_new = s1 + s2;
+    T rad = ms_new + h.epsilon;
+    T den = sqrt_rn(rad);
+    return h.lambda / den;
 }
 
 // v' = momentum * v_t - lr * (s * grad_scale + r);  w' = w_t + v'
@@ -160,61 +202,84 @@ __device__ __forceinline__ void update_global(T w0, T v0, T s, T r, const Hyp &h
 }
 
 // ---------------------------------------------------------------------------
-// one chunk, fixed worker count W_T: U groups in flight per lane, every load
-// issued before the first store (the compiler cannot prove the outputs do not
-// alias the inputs, so the order is written out by hand).
+// one tile, fixed worker count W_T: every load is issued before the first
+// store (the compiler cannot prove the outputs do not alias the inputs, so the
+// order is written out by hand).
 // ---------------------------------------------------------------------------
-template <int W_T, int MODE>
+template <int W_T>
 struct Ptrs {
     uint64_t w;
     uint64_t v;
     uint64_t g[W_T];
     uint64_t u[W_T];
+    uint64_t ms[W_T];
 };
 
-template <int W_T, int MODE, int U, typename T>
-__device__ __forceinline__ void apply_fixed(const Ptrs<W_T, MODE> &p, unsigned i, const Hyp &h)
+template <int W_T, int MODE, int RULE, typename T>
+__device__ __forceinline__ void apply_fixed(const Ptrs<W_T> &p, unsigned i, const Hyp &h)
 {
     constexpr bool need_v = (MODE != MODE_LOCAL);
     constexpr bool need_u = (MODE != MODE_GLOBAL);
-    T w0[U], v0[U], g[U][W_T];
+    constexpr bool local_rule = (MODE == MODE_OD || MODE == MODE_LOCAL);
+    constexpr bool need_u_old = local_rule && RULE != RULE_SGD;
+    constexpr bool need_ms = local_rule && RULE == RULE_DCA;
+
+    T w0, v0, g[W_T], u_old[W_T], ms_old[W_T];
+    w0 = load<ODSGD_NT_STATE_LD, T>(p.w, i);
+    if constexpr (need_v)
+        v0 = load<ODSGD_NT_STATE_LD, T>(p.v, i);
 #pragma unroll
-    for (int j = 0; j < U; ++j) {
-        w0[j] = load<ODSGD_NT_STATE_LD, T>(p.w, i + j * kBlock);
-        if constexpr (need_v)
-            v0[j] = load<ODSGD_NT_STATE_LD, T>(p.v, i + j * kBlock);
+    for (int m = 0; m < W_T; ++m)
+        g[m] = load<ODSGD_NT_GRAD, T>(p.g[m], i);
+    if constexpr (need_u_old) {
 #pragma unroll
         for (int m = 0; m < W_T; ++m)
-            g[j][m] = load<ODSGD_NT_GRAD, T>(p.g[m], i + j * kBlock);
+            u_old[m] = load<ODSGD_NT_LOCAL, T>(p.u[m], i);
+    }
+    if constexpr (need_ms) {
+#pragma unroll
+        for (int m = 0; m < W_T; ++m)
+            ms_old[m] = load<ODSGD_NT_LOCAL, T>(p.ms[m], i);
     }
 
+    T r = h.weight_decay * w0;
+    T w1 = w0, v1;
+    if constexpr (MODE != MODE_LOCAL) {
+        T s = g[0];
 #pragma unroll
-    for (int j = 0; j < U; ++j) {
-        T r = h.weight_decay * w0[j];
-        T w1 = w0[j], v1;
-        if constexpr (MODE != MODE_LOCAL) {
-            T s = g[j][0];
+        for (int m = 1; m < W_T; ++m)
+            s = s + g[m];
+        update_global(w0, v0, s, r, h, w1, v1);
+    }
+    if constexpr (need_u) {
 #pragma unroll
-            for (int m = 1; m < W_T; ++m)
-                s = s + g[j][m];
-            update_global(w0[j], v0[j], s, r, h, w1, v1);
-        }
-        if constexpr (need_u) {
-#pragma unroll
-            for (int m = 0; m < W_T; ++m) {
-                T um = (MODE == MODE_SSGD) ? w1 : update_local(w0[j], g[j][m], r, h.local_lr);
-                store<ODSGD_NT_LOCAL, T>(p.u[m], i + j * kBlock, um);
+        for (int m = 0; m < W_T; ++m) {
+            T um;
+            if constexpr (MODE == MODE_SSGD) {
+                um = w1;
+            } else if constexpr (RULE == RULE_SGD) {
+                um = update_local(w0, g[m], r, h.local_lr);
+            } else if constexpr (RULE == RULE_DCC) {
+                T gg = g[m] * g[m];
+                um = update_local_dc(w0, g[m], gg, u_old[m], r, h.lambda, h.local_lr);
+            } else {
+                T gg = g[m] * g[m];
+                T ms_new;
+                T lam = mean_square_step(gg, ms_old[m], h, ms_new);
+                store<ODSGD_NT_LOCAL, T>(p.ms[m], i, ms_new);
+                um = update_local_dc(w0, g[m], gg, u_old[m], r, lam, h.local_lr);
             }
+            store<ODSGD_NT_LOCAL, T>(p.u[m], i, um);
         }
-        if constexpr (MODE != MODE_LOCAL) {
-            store<ODSGD_NT_STATE_ST, T>(p.v, i + j * kBlock, v1);
-            store<ODSGD_NT_STATE_ST, T>(p.w, i + j * kBlock, w1);
-        }
+    }
+    if constexpr (MODE != MODE_LOCAL) {
+        store<ODSGD_NT_STATE_ST, T>(p.v, i, v1);
+        store<ODSGD_NT_STATE_ST, T>(p.w, i, w1);
     }
 }
 
 // any worker count: pointers are fetched from the table inside the worker loop
-template <int MODE, typename T>
+template <int MODE, int RULE, typename T>
 __device__ __forceinline__ void apply_generic(ptr_table_t row, uint64_t byte_off, int wtot, int wfirst,
                                               int wcount, unsigned i, const Hyp &h)
 {
@@ -227,8 +292,25 @@ __device__ __forceinline__ void apply_generic(ptr_table_t row, uint64_t byte_off
         T gm = load<ODSGD_NT_GRAD, T>(row[2 + wfirst + m] + byte_off, i);
         s = (m == 0) ? gm : s + gm;
         if constexpr (MODE == MODE_OD || MODE == MODE_LOCAL) {
-            store<ODSGD_NT_LOCAL, T>(row[2 + wtot + wfirst + m] + byte_off, i,
-                                     update_local(w0, gm, r, h.local_lr));
+            const uint64_t pu = row[2 + wtot + wfirst + m] + byte_off;
+            T um;
+            if constexpr (RULE == RULE_SGD) {
+                um = update_local(w0, gm, r, h.local_lr);
+            } else if constexpr (RULE == RULE_DCC) {
+                T u_old = load<ODSGD_NT_LOCAL, T>(pu, i);
+                T gg = gm * gm;
+                um = update_local_dc(w0, gm, gg, u_old, r, h.lambda, h.local_lr);
+            } else {
+                const uint64_t pms = row[2 + 2 * wtot + wfirst + m] + byte_off;
+                T u_old = load<ODSGD_NT_LOCAL, T>(pu, i);
+                T ms_old = load<ODSGD_NT_LOCAL, T>(pms, i);
+                T gg = gm * gm;
+                T ms_new;
+                T lam = mean_square_step(gg, ms_old, h, ms_new);
+                store<ODSGD_NT_LOCAL, T>(pms, i, ms_new);
+                um = update_local_dc(w0, gm, gg, u_old, r, lam, h.local_lr);
+            }
+            store<ODSGD_NT_LOCAL, T>(pu, i, um);
         }
     }
     if constexpr (MODE != MODE_LOCAL) {
@@ -248,14 +330,15 @@ __device__ __forceinline__ void apply_generic(ptr_table_t row, uint64_t byte_off
 // ---------------------------------------------------------------------------
 // the kernel: grid-stride over the chunk table
 // ---------------------------------------------------------------------------
-template <int W_T, int MODE>
+template <int W_T, int MODE, int RULE>
 __global__ void __launch_bounds__(kBlock) odsgd_kernel(KernelArgs a)
 {
     const chunk_table_t chunks = (chunk_table_t)a.chunks;
     const ptr_table_t ptrs = (ptr_table_t)a.ptrs;
-    const Hyp h{a.lr, a.local_lr, a.momentum, a.weight_decay, a.grad_scale};
+    const Hyp h{a.lr, a.local_lr, a.momentum, a.weight_decay, a.grad_scale,
+                a.lambda, a.ms_decay, a.one_minus_ms_decay, a.epsilon};
     const unsigned tid = threadIdx.x;
-    const int stride = 2 + 2 * a.wtot;
+    const int stride = 2 + 3 * a.wtot;
 
     // Workgroup b takes chunk b.  The dispatcher hands consecutive workgroups to
     // the 8 XCDs in turn, so at any moment the chip works on one narrow, sliding
@@ -271,23 +354,25 @@ __global__ void __launch_bounds__(kBlock) odsgd_kernel(KernelArgs a)
         const unsigned nvec = vec ? (count >> 2) : 0u;
 
         if constexpr (W_T > 0) {
-            Ptrs<W_T, MODE> p;
+            Ptrs<W_T> p;
             p.w = row[0] + byte_off;
             p.v = row[1] + byte_off;
 #pragma unroll
             for (int m = 0; m < W_T; ++m) {
                 p.g[m] = row[2 + a.wfirst + m] + byte_off;
                 p.u[m] = row[2 + a.wtot + a.wfirst + m] + byte_off;
+                if constexpr (RULE == RULE_DCA)
+                    p.ms[m] = row[2 + 2 * a.wtot + a.wfirst + m] + byte_off;
             }
             for (unsigned i = tid; i < nvec; i += kBlock)
-                apply_fixed<W_T, MODE, 1, f4>(p, i, h);
+                apply_fixed<W_T, MODE, RULE, f4>(p, i, h);
             for (unsigned t = nvec * 4 + tid; t < count; t += kBlock)
-                apply_fixed<W_T, MODE, 1, float>(p, t, h);
+                apply_fixed<W_T, MODE, RULE, float>(p, t, h);
         } else {
             for (unsigned i = tid; i < nvec; i += kBlock)
-                apply_generic<MODE, f4>(row, byte_off, a.wtot, a.wfirst, a.wcount, i, h);
+                apply_generic<MODE, RULE, f4>(row, byte_off, a.wtot, a.wfirst, a.wcount, i, h);
             for (unsigned t = nvec * 4 + tid; t < count; t += kBlock)
-                apply_generic<MODE, float>(row, byte_off, a.wtot, a.wfirst, a.wcount, t, h);
+                apply_generic<MODE, RULE, float>(row, byte_off, a.wtot, a.wfirst, a.wcount, t, h);
         }
     }
 }
@@ -371,7 +456,7 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 size_t ptr_table_bytes(int num_tensors, int num_workers)
 {
-    return align_up((size_t)num_tensors * (2 + 2 * (size_t)num_workers) * sizeof(uint64_t), 256);
+    return align_up((size_t)num_tensors * (2 + 3 * (size_t)num_workers) * sizeof(uint64_t), 256);
 }
 
 struct Range {
@@ -398,27 +483,37 @@ bool ranges_alias(std::vector<Range> &r)
 
 using KernelFn = void (*)(KernelArgs);
 
-template <int MODE>
-KernelFn pick_kernel(int wcount)
+template <int MODE, int RULE>
+KernelFn pick_by_workers(int wcount)
 {
     switch (wcount) {
-    case 1: return odsgd_kernel<1, MODE>;
-    case 2: return odsgd_kernel<2, MODE>;
-    case 4: return odsgd_kernel<4, MODE>;
-    case 8: return odsgd_kernel<8, MODE>;
-    case 12: return odsgd_kernel<12, MODE>;
-    case 16: return odsgd_kernel<16, MODE>;
-    default: return odsgd_kernel<0, MODE>;
+    case 1: return odsgd_kernel<1, MODE, RULE>;
+    case 2: return odsgd_kernel<2, MODE, RULE>;
+    case 4: return odsgd_kernel<4, MODE, RULE>;
+    case 8: return odsgd_kernel<8, MODE, RULE>;
+    case 12: return odsgd_kernel<12, MODE, RULE>;
+    case 16: return odsgd_kernel<16, MODE, RULE>;
+    default: return odsgd_kernel<0, MODE, RULE>;
     }
 }
 
-KernelFn pick_kernel(int mode, int wcount)
+template <int MODE>
+KernelFn pick_by_rule(int rule, int wcount)
+{
+    switch (rule) {
+    case RULE_DCC: return pick_by_workers<MODE, RULE_DCC>(wcount);
+    case RULE_DCA: return pick_by_workers<MODE, RULE_DCA>(wcount);
+    default: return pick_by_workers<MODE, RULE_SGD>(wcount);
+    }
+}
+
+KernelFn pick_kernel(int mode, int rule, int wcount)
 {
     switch (mode) {
-    case MODE_OD: return pick_kernel<MODE_OD>(wcount);
-    case MODE_SSGD: return pick_kernel<MODE_SSGD>(wcount);
-    case MODE_GLOBAL: return pick_kernel<MODE_GLOBAL>(wcount);
-    default: return pick_kernel<MODE_LOCAL>(wcount);
+    case MODE_OD: return pick_by_rule<MODE_OD>(rule, wcount);
+    case MODE_LOCAL: return pick_by_rule<MODE_LOCAL>(rule, wcount);
+    case MODE_SSGD: return pick_by_workers<MODE_SSGD, RULE_SGD>(wcount);
+    default: return pick_by_workers<MODE_GLOBAL, RULE_SGD>(wcount);
     }
 }
 
@@ -436,6 +531,9 @@ struct odsgd_handle {
     Tuning tuning;
     int64_t iteration;
     int64_t warmup_steps;
+    odsgd_local_rule rule;               // local updater of MODE_OD / MODE_LOCAL
+    std::vector<int64_t> numel;
+    std::vector<Range> ranges;           // every registered buffer, for alias checks of later registrations
     std::vector<unsigned char> staging;  // host image of the tables (kept alive for the upload)
 };
 
@@ -452,8 +550,16 @@ size_t occupancy_cap_lds_bytes(const odsgd_handle *h, int mode, int wcount)
         return 0;
     if (waves == 0) {
         // memory instructions (loads + stores) one lane issues per tile
-        const int loads = (mode == MODE_LOCAL) ? wcount + 1 : wcount + 2;
-        const int stores = (mode == MODE_GLOBAL) ? 2 : (mode == MODE_LOCAL) ? wcount : wcount + 2;
+        int loads = (mode == MODE_LOCAL) ? wcount + 1 : wcount + 2;
+        int stores = (mode == MODE_GLOBAL) ? 2 : (mode == MODE_LOCAL) ? wcount : wcount + 2;
+        if (mode == MODE_OD || mode == MODE_LOCAL) {
+            if (h->rule.rule != ODSGD_LOCAL_SGD)
+                loads += wcount;  // previous local weights
+            if (h->rule.rule == ODSGD_LOCAL_DCASGD_A) {
+                loads += wcount;  // MeanSquare state in ...
+                stores += wcount; // ... and out
+            }
+        }
         const int ops = loads + stores;
         // nearest integer; rounded up once a tile spans many arrays
         waves = (ops < 24) ? (ODSGD_INFLIGHT_MEMOPS_PER_CU + ops / 2) / ops
@@ -488,11 +594,15 @@ int launch(odsgd_handle *h, int mode, int wfirst, int wcount, const odsgd_hyper 
     a.momentum = hy->momentum;
     a.weight_decay = hy->weight_decay;
     a.grad_scale = (hy->grad_scale <= 0.0f) ? 1.0f / (float)h->num_workers : hy->grad_scale;
+    a.lambda = h->rule.lambda;
+    a.ms_decay = h->rule.ms_decay;
+    a.one_minus_ms_decay = 1.0f - h->rule.ms_decay;
+    a.epsilon = h->rule.epsilon;
 
     int64_t grid = h->nchunks;
     if (h->tuning.blocks_per_cu > 0)
         grid = std::min<int64_t>(grid, (int64_t)h->tuning.blocks_per_cu * h->num_cus);
-    KernelFn fn = pick_kernel(mode, wcount);
+    KernelFn fn = pick_kernel(mode, h->rule.rule, wcount);
     const size_t lds = occupancy_cap_lds_bytes(h, mode, wcount);
     hipLaunchKernelGGL(fn, dim3((unsigned)grid), dim3(kBlock), lds, (hipStream_t)stream, a);
     hipError_t e = hipGetLastError();
@@ -540,7 +650,8 @@ int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel, float 
         return err;
 
     const int W = num_workers;
-    const int stride = 2 + 2 * W;
+    const int stride = 2 + 3 * W;
+    const int registered = 2 + 2 * W;  // the MeanSquare columns stay null until a rule registers them
 
     // pointer checks: non-null and 4-byte aligned where the tensor is not empty
     std::vector<Range> ranges;
@@ -550,7 +661,7 @@ int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel, float 
         if (numel[k] == 0)
             continue;
         const size_t bytes = (size_t)numel[k] * sizeof(float);
-        for (int j = 0; j < stride; ++j) {
+        for (int j = 0; j < registered; ++j) {
             const void *p = j == 0   ? (const void *)w[k]
                             : j == 1 ? (const void *)mom[k]
                             : j < 2 + W ? (const void *)grads[j - 2][k]
@@ -573,8 +684,11 @@ int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel, float 
     if (workspace_bytes < ptr_bytes + chunk_bytes)
         return ODSGD_ENOSPC;
     ranges.push_back(Range{(uintptr_t)workspace, (uintptr_t)workspace + ptr_bytes + chunk_bytes, true});
-    if (ranges_alias(ranges))
-        return ODSGD_EALIAS;
+    {
+        std::vector<Range> sorted = ranges;
+        if (ranges_alias(sorted))
+            return ODSGD_EALIAS;
+    }
 
     odsgd_handle *h = new (std::nothrow) odsgd_handle();
     if (!h)
@@ -585,6 +699,9 @@ int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel, float 
     h->tuning = tuning;
     h->iteration = 0;
     h->warmup_steps = 0;
+    h->rule = odsgd_local_rule{ODSGD_LOCAL_SGD, 0.0f, 0.0f, 0.0f};
+    h->numel.assign(numel, numel + num_tensors);
+    h->ranges = std::move(ranges);
     h->d_ptrs = workspace;
     h->d_chunks = (const unsigned char *)workspace + ptr_bytes;
 
@@ -693,6 +810,57 @@ int odsgd_step(odsgd_handle *h, const odsgd_hyper *hyper, void *stream)
     if (rc == ODSGD_OK)
         ++h->iteration;
     return rc;
+}
+
+int odsgd_set_local_rule(odsgd_handle *h, const odsgd_local_rule *rule, float *const *const *mean_square,
+                         void *stream)
+{
+    if (!h || !rule)
+        return ODSGD_EINVAL;
+    if (rule->rule != ODSGD_LOCAL_SGD && rule->rule != ODSGD_LOCAL_DCASGD_C && rule->rule != ODSGD_LOCAL_DCASGD_A)
+        return ODSGD_EINVAL;
+    if (rule->rule == ODSGD_LOCAL_DCASGD_A) {
+        if (!mean_square)
+            return ODSGD_EINVAL;
+        const int W = h->num_workers, K = h->num_tensors;
+        const int stride = 2 + 3 * W;
+        std::vector<Range> all = h->ranges;
+        std::vector<uint64_t> cols((size_t)K * W, 0);
+        for (int m = 0; m < W; ++m) {
+            if (!mean_square[m])
+                return ODSGD_EINVAL;
+            for (int k = 0; k < K; ++k) {
+                if (h->numel[k] == 0)
+                    continue;
+                const uintptr_t a = (uintptr_t)mean_square[m][k];
+                if (!a)
+                    return ODSGD_EINVAL;
+                // a tensor's 128-bit path was chosen at init from its other pointers, so
+                // the state must be able to follow it
+                if (a % 16 != 0)
+                    return ODSGD_EALIGN;
+                all.push_back(Range{a, a + (size_t)h->numel[k] * sizeof(float), true});
+                cols[(size_t)k * W + m] = (uint64_t)a;
+            }
+        }
+        std::vector<Range> sorted = all;
+        if (ranges_alias(sorted))
+            return ODSGD_EALIAS;
+        // upload the MeanSquare columns of every pointer-table row
+        hipError_t e = hipMemcpy2DAsync((unsigned char *)const_cast<void *>(h->d_ptrs) + (size_t)(2 + 2 * W) * sizeof(uint64_t),
+                                        (size_t)stride * sizeof(uint64_t), cols.data(), (size_t)W * sizeof(uint64_t),
+                                        (size_t)W * sizeof(uint64_t), (size_t)K, hipMemcpyHostToDevice,
+                                        (hipStream_t)stream);
+        if (e == hipSuccess)
+            e = hipStreamSynchronize((hipStream_t)stream);
+        if (e != hipSuccess) {
+            g_last_hip_error = e;
+            return ODSGD_EHIP;
+        }
+        h->ranges = std::move(all);
+    }
+    h->rule = *rule;
+    return ODSGD_OK;
 }
 
 int odsgd_set_warmup(odsgd_handle *h, int64_t warmup_steps)
