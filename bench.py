@@ -70,6 +70,45 @@ def time_gpu(wl_mod, B, torch, name, steps, warmup):
     }, st
 
 
+def time_entry_points(wl_mod, B, torch, name, st, steps=20, warmup=3):
+    """The other entry points and local updaters on the same resident state, each
+    against its own algorithmic bytes per parameter."""
+    w = wl_mod.WORKLOADS[name]
+    W, N = w.num_workers, wl_mod.total_params(w)
+    hy = B.odsgd_hyper(*w.hyper)
+    stream = torch.cuda.current_stream()
+    ms = [[torch.zeros_like(t) for t in st["w"]] for _ in range(W)]
+    eng = B.Engine(st["w"], st["v"], st["g"], st["u"])
+    cases = [
+        ("odsgd_local_update(-1) sgd", 4 * (2 * W + 1), None, lambda: eng.local_update(-1, hy, stream)),
+        ("odsgd_global_update", 4 * (W + 4), None, lambda: eng.global_update(hy, stream)),
+        ("odsgd_ssgd_step", 8 * (W + 2), None, lambda: eng.ssgd_step(hy, stream)),
+        ("odsgd_step dcasgd_c", 4 * (3 * W + 4), (B.ODSGD_LOCAL_DCASGD_C, 0.04, 0.0, 0.0, None),
+         lambda: eng.step(hy, stream)),
+        ("odsgd_step dcasgd_a", 4 * (5 * W + 4), (B.ODSGD_LOCAL_DCASGD_A, 2.0, 0.95, 1e-7, ms),
+         lambda: eng.step(hy, stream)),
+    ]
+    out = {}
+    for label, bpp, rule, fn in cases:
+        if rule is not None:
+            eng.set_local_rule(rule[0], lam=rule[1], ms_decay=rule[2], epsilon=rule[3], mean_square=rule[4])
+        for _ in range(warmup):
+            fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        torch.cuda.synchronize()
+        ev[0].record(stream)
+        for _ in range(steps):
+            fn()
+        ev[1].record(stream)
+        torch.cuda.synchronize()
+        ms_launch = ev[0].elapsed_time(ev[1]) / steps
+        gbps = bpp * N / (ms_launch * 1e-3) / 1e9
+        out[label] = {"bytes_per_param": bpp, "kernel_ms_mean": ms_launch, "hbm_gbps": gbps,
+                      "hbm_frac": gbps / HBM_PEAK_GBPS}
+    eng.close()
+    return out
+
+
 def time_copy_probe(B, torch, steps, warmup, gib=1.0):
     """Plain copy of `gib` GiB (read) + `gib` GiB (write) per launch, same tile shape as the update kernel."""
     n = int(gib * (1 << 30)) // 4
@@ -134,6 +173,8 @@ def main():
     ap.add_argument("--others", default="vgg16,alexnet",
                     help="comma list of further workloads measured in the same run ('' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-entry-points", action="store_true",
+                    help="skip the secondary measurements of the other entry points / local updaters")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only the plain copy kernel of known traffic (counter calibration)")
     args = ap.parse_args()
@@ -159,6 +200,7 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(wl_mod, args.workload, st)
+    entry_points = {} if args.no_entry_points else time_entry_points(wl_mod, B, torch, args.workload, st)
     del st
     torch.cuda.empty_cache()
 
@@ -197,6 +239,7 @@ def main():
                      "plain_copy_gbps_same_box": probe["gbps"],
                      "frac_of_plain_copy": main_s["hbm_gbps"] / probe["gbps"]},
         "cpu_baseline": cpu,
+        "other_entry_points": entry_points,
         "other_workloads": others,
         "paper_context": PAPER_CONTEXT,
     }

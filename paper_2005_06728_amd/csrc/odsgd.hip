@@ -564,6 +564,10 @@ size_t occupancy_cap_lds_bytes(const odsgd_handle *h, int mode, int wcount)
         // nearest integer; rounded up once a tile spans many arrays
         waves = (ops < 24) ? (ODSGD_INFLIGHT_MEMOPS_PER_CU + ops / 2) / ops
                            : (ODSGD_INFLIGHT_MEMOPS_PER_CU + ops - 1) / ops;
+        // the adaptive rule spends a correctly rounded sqrt and divide per element and
+        // worker: more wavefronts are needed to hide that arithmetic
+        if ((mode == MODE_OD || mode == MODE_LOCAL) && h->rule.rule == ODSGD_LOCAL_DCASGD_A)
+            waves = std::max(5, (170 + ops / 2) / ops);
         if (waves > 16)
             return 0;  // few streams: full occupancy is best
     }
