@@ -344,7 +344,7 @@ __global__ void __launch_bounds__(kBlock) odsgd_kernel(KernelArgs a)
     // the 8 XCDs in turn, so at any moment the chip works on one narrow, sliding
     // window of each array; giving every XCD a contiguous range of its own
     // instead was measured 15 % slower.
-    for (int c = blockIdx.x; c < a.nchunks; c += gridDim.x) {
+    for (unsigned c = blockIdx.x; c < (unsigned)a.nchunks; c += gridDim.x) {
         const u4 d = chunks[c];
         const uint32_t tensor = d.x & ~kVecFlag;
         const bool vec = (d.x & kVecFlag) != 0;
@@ -608,7 +608,9 @@ int launch(odsgd_handle *h, int mode, int wfirst, int wcount, const odsgd_hyper 
     a.one_minus_ms_decay = 1.0f - h->rule.ms_decay;
     a.epsilon = h->rule.epsilon;
 
-    int64_t grid = h->nchunks;
+    // one workgroup per chunk; beyond 2^25 workgroups (2^31 threads, the launch
+    // limit is 2^32) the kernel's grid-stride loop takes over
+    int64_t grid = std::min<int64_t>(h->nchunks, (int64_t)1 << 25);
     if (h->tuning.blocks_per_cu > 0)
         grid = std::min<int64_t>(grid, (int64_t)h->tuning.blocks_per_cu * h->num_cus);
     KernelFn fn = pick_kernel(mode, h->rule.rule, wcount);
