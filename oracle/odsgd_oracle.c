@@ -164,6 +164,35 @@ void ODSGD_NAME(odsgd_oracle_local_dcasgd_a)(int64_t n, int M, const real *w,
 }
 
 /*
+ * Local momentum-SGD updater.  Section 4.2 runs the local SGD updater with "the
+ * learning rate and momentum of SSGD", which is read here as a per-worker local
+ * velocity lv_m that accumulates the worker's own gradients:
+ *   lv_m <- local_momentum * lv_m - local_lr * (g_m + r) ;   u_m <- w + lv_m.
+ * With local_momentum = 0 this is exactly the plain SGD local updater.
+ */
+void ODSGD_NAME(odsgd_oracle_local_momentum)(int64_t n, int M, const real *w,
+                                             const real *const *g, real *const *u,
+                                             real *const *lv, int worker,
+                                             real local_lr, real weight_decay,
+                                             real local_momentum)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        real w0 = w[i];
+        real r = weight_decay * w0;
+        for (int m = 0; m < M; ++m) {
+            if (worker >= 0 && m != worker)
+                continue;
+            real dm = g[m][i] + r;
+            real am = local_momentum * lv[m][i];
+            real pm = local_lr * dm;
+            real lv1 = am - pm;
+            lv[m][i] = lv1;
+            u[m][i] = w0 + lv1;
+        }
+    }
+}
+
+/*
  * Server-side global update (Alg. 1, "Update w_t with aggregated gradient"):
  * M-way sum in ascending worker order, scale, coupled weight decay,
  * momentum-SGD step in velocity form.  w and v are updated in place.

@@ -96,6 +96,24 @@ def local_update_dcasgd_a(w, g, u, ms, local_lr, weight_decay, lam, ms_decay, ep
            ct(local_lr), ct(weight_decay), ct(lam), ct(ms_decay), ct(epsilon))
 
 
+def local_update_momentum(w, g, u, lv, local_lr, weight_decay, local_momentum, worker=-1):
+    """Local momentum-SGD updater; lv[m][k] is worker m's local velocity."""
+    M = len(g)
+    for k in range(len(w)):
+        dt = w[k].dtype
+        ct, sfx = _CT[dt]
+        n = w[k].shape[0]
+        gk = [g[m][k] for m in range(M)]
+        uk = [u[m][k] for m in range(M)]
+        lk = [lv[m][k] for m in range(M)]
+        _check([w[k]] + gk + uk + lk, dt, n)
+        fn = getattr(lib(), "odsgd_oracle_local_momentum_" + sfx)
+        fn.restype = None
+        fn(ctypes.c_int64(n), ctypes.c_int(M), w[k].ctypes.data_as(ctypes.POINTER(ct)),
+           _ptr_array(gk, ct), _ptr_array(uk, ct), _ptr_array(lk, ct), ctypes.c_int(worker),
+           ct(local_lr), ct(weight_decay), ct(local_momentum))
+
+
 def global_update(w, v, g, lr, momentum, weight_decay, grad_scale=0.0):
     """Server-side global update, tensor list form. w, v: [K], g: [M][K]."""
     M = len(g)
@@ -154,7 +172,8 @@ def step(i, warmup_steps, w, v, g, u, lr, local_lr, momentum, weight_decay, grad
     i < warmup_steps, one-step-delay iteration from i == warmup_steps on.
 
     rule: None for the SGD local updater, ("dcasgd_c", lam) or
-    ("dcasgd_a", lam, ms_decay, epsilon, ms) for the delay-compensated ones.  By
+    ("dcasgd_a", lam, ms_decay, epsilon, ms) for the delay-compensated ones,
+    ("momentum", local_momentum, lv) for the local momentum-SGD updater.  By
     definition the OD iteration is the local update followed by the global one."""
     if i < warmup_steps:
         ssgd_step(w, v, g, u, lr, momentum, weight_decay, grad_scale)
@@ -165,6 +184,8 @@ def step(i, warmup_steps, w, v, g, u, lr, local_lr, momentum, weight_decay, grad
             local_update_dcasgd_c(w, g, u, local_lr, weight_decay, rule[1])
         elif rule[0] == "dcasgd_a":
             local_update_dcasgd_a(w, g, u, rule[4], local_lr, weight_decay, rule[1], rule[2], rule[3])
+        elif rule[0] == "momentum":
+            local_update_momentum(w, g, u, rule[2], local_lr, weight_decay, rule[1])
         else:
             raise ValueError(rule[0])
         global_update(w, v, g, lr, momentum, weight_decay, grad_scale)

@@ -173,3 +173,69 @@ def test_schedule_with_rule_first_compensated_update_at_wp():
         else:
             assert not same_bits(u[0][0], u2[0][0])
         u2 = [copy_list(r) for r in u]  # keep the two runs' worker state aligned for the next comparison
+
+
+# --------------------------------------------------------------------------
+# local momentum-SGD updater (Section 4.2: local SGD with the server's momentum)
+# --------------------------------------------------------------------------
+def test_local_momentum_zero_is_plain_sgd_updater_bitwise():
+    rng = np.random.default_rng(6)
+    w, g, u, _ = _rand(rng, 40, 3)
+    lv = [[rng.normal(0, 1e-3, 40).astype(F32)] for _ in range(3)]
+    ref = [[np.zeros(40, F32)] for _ in range(3)]
+    oracle.local_update(w, g, ref, 0.3, 1e-3)
+    oracle.local_update_momentum(w, g, u, lv, 0.3, 1e-3, 0.0)
+    for m in range(3):
+        assert same_bits(u[m][0], ref[m][0])
+        # the stored velocity is the step just taken: u = w + lv
+        assert same_bits((w[0] + lv[m][0]).astype(F32), u[m][0])
+
+
+def test_single_worker_local_velocity_tracks_the_server_bitwise():
+    """W=1, grad_scale=1, local_lr=lr, local momentum = server momentum, both velocities
+    zero at the start and the gradient fed independent of the weights: worker and server
+    perform the same operations, so u_0 == w_{t+1} and lv_0 == v after every iteration."""
+    rng = np.random.default_rng(7)
+    n = 30
+    w = [rng.normal(0, 1, n).astype(F32)]
+    v = [np.zeros(n, F32)]
+    u = [[w[0].copy()]]
+    lv = [[np.zeros(n, F32)]]
+    for i in range(6):
+        g = [[rng.normal(0, 0.1, n).astype(F32)]]
+        oracle.step(i, 0, w, v, g, u, 0.1, 0.1, 0.9, 1e-3, 1.0, rule=("momentum", 0.9, lv))
+        assert same_bits(u[0][0], w[0]) and same_bits(lv[0][0], v[0])
+
+
+def test_local_momentum_constant_gradient_closed_form():
+    """Constant g, wd = 0, lv_0 = 0: lv_t = -ll g (1 - mu^t)/(1 - mu); u_t = w + lv_t."""
+    ll, mu, g0 = F(1, 8), F(1, 2), F(3, 4)
+    w = [arr([2.0], np.float64)]
+    u = [[arr([0.0], np.float64)]]
+    lv = [[arr([0.0], np.float64)]]
+    for t in range(1, 12):
+        oracle.local_update_momentum(w, [[arr([float(g0)], np.float64)]], u, lv, float(ll), 0.0, float(mu))
+        expect = -ll * g0 * (1 - mu ** t) / (1 - mu)
+        assert lv[0][0][0] == float(expect) and u[0][0][0] == float(2 + expect)  # dyadic: exact
+
+
+def test_local_momentum_against_library_momentum_sgd():
+    """A worker whose pulled weights are its own previous result (server frozen out:
+    w := u after every step) runs textbook momentum SGD; cross-check with torch.optim.SGD."""
+    import torch
+    rng = np.random.default_rng(8)
+    n, ll, mu, wd = 9, 0.05, 0.9, 1e-2
+    a = rng.uniform(0.5, 2.0, n)
+    x0 = rng.normal(0, 1, n)
+    p = torch.nn.Parameter(torch.tensor(x0))
+    opt = torch.optim.SGD([p], lr=ll, momentum=mu, weight_decay=wd)
+    w = [x0.copy()]
+    u = [[np.zeros(n)]]
+    lv = [[np.zeros(n)]]
+    for _ in range(20):
+        g = a * w[0]
+        oracle.local_update_momentum(w, [[g]], u, lv, ll, wd, mu)
+        w[0][...] = u[0][0]
+        p.grad = torch.tensor(a * p.detach().numpy())
+        opt.step()
+        assert max_rel_err(w[0], p.detach().numpy()) < 1e-12

@@ -37,12 +37,12 @@ MUTANTS = [
     ("weight_step_sign", "real w1 = w0 + v1;", "real w1 = w0 - v1;", 1),
     ("lr_dropped", "real b = lr * d;", "real b = d;", 1),
     ("stores_swapped", "v[i] = v1;\n        w[i] = w1;", "v[i] = w1;\n        w[i] = v1;", 1),
-    ("local_decay_dropped", "real dm = g[m][i] + r;", "real dm = g[m][i];", 1),
-    ("local_decay_sign", "real dm = g[m][i] + r;", "real dm = g[m][i] - r;", 1),
+    ("local_decay_dropped", "real dm = g[m][i] + r;\n            real pm", "real dm = g[m][i];\n            real pm", 1),
+    ("local_decay_sign", "real dm = g[m][i] + r;\n            real pm", "real dm = g[m][i] - r;\n            real pm", 1),
     ("local_step_sign", "real pm = local_lr * dm;\n            u[m][i] = w0 - pm;",
      "real pm = local_lr * dm;\n            u[m][i] = w0 + pm;", 1),
     ("local_uses_global_lr", "(n, M, w, g, u, -1, local_lr, weight_decay);", "(n, M, w, g, u, -1, lr, weight_decay);", 1),
-    ("local_worker_filter_inverted", "if (worker >= 0 && m != worker)", "if (worker >= 0 && m == worker)", 3),
+    ("local_worker_filter_inverted", "if (worker >= 0 && m != worker)", "if (worker >= 0 && m == worker)", 4),
     ("local_reads_new_weights",
      "ODSGD_NAME(odsgd_oracle_local)(n, M, w, g, u, -1, local_lr, weight_decay);\n"
      "    ODSGD_NAME(odsgd_oracle_global)(n, M, w, v, g, lr, momentum, weight_decay,\n"
@@ -62,6 +62,11 @@ MUTANTS = [
     ("dca_no_square_root", "real den = ODSGD_SQRT(rad);", "real den = rad;", 1),
     ("dca_multiplies_by_root", "real lam = lambda / den;", "real lam = lambda * den;", 1),
     ("dca_uses_plain_lambda", "real c2 = c1 * lam;", "real c2 = c1 * lambda;", 1),
+    ("local_momentum_dropped", "real am = local_momentum * lv[m][i];", "real am = lv[m][i];", 1),
+    ("local_velocity_sign", "real lv1 = am - pm;", "real lv1 = am + pm;", 1),
+    ("local_velocity_not_stored", "lv[m][i] = lv1;", ";", 1),
+    ("local_velocity_subtracted", "u[m][i] = w0 + lv1;", "u[m][i] = w0 - lv1;", 1),
+    ("local_momentum_decay_dropped", "real dm = g[m][i] + r;\n            real am", "real dm = g[m][i];\n            real am", 1),
 ]
 FLAG_MUTANTS = [("fused_multiply_add", ["-ffp-contract=fast", "-mfma"])]
 
