@@ -89,11 +89,14 @@ def time_entry_points(wl_mod, B, torch, name, st, steps=20, warmup=3):
          lambda: eng.step(hy, stream)),
         ("odsgd_step dcasgd_a", 4 * (5 * W + 4), (B.ODSGD_LOCAL_DCASGD_A, 2.0, 0.95, 1e-7, ms),
          lambda: eng.step(hy, stream)),
+        ("odsgd_step local momentum", 4 * (4 * W + 4), (B.ODSGD_LOCAL_SGD_MOMENTUM, 0.0, 0.0, 0.0, ms),
+         lambda: eng.step(hy, stream)),
     ]
     out = {}
     for label, bpp, rule, fn in cases:
         if rule is not None:
-            eng.set_local_rule(rule[0], lam=rule[1], ms_decay=rule[2], epsilon=rule[3], mean_square=rule[4])
+            eng.set_local_rule(rule[0], lam=rule[1], ms_decay=rule[2], epsilon=rule[3], mean_square=rule[4],
+                               local_momentum=0.9)
         for _ in range(warmup):
             fn()
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]

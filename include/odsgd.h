@@ -151,27 +151,35 @@ int odsgd_ssgd_step(odsgd_handle *h, const odsgd_hyper *hyper, void *stream);
  *   ODSGD_LOCAL_DCASGD_C  local_w[m] = w - local_lr*((g + r) + ((g*g)*(w - u_old))*lambda)
  *   ODSGD_LOCAL_DCASGD_A  ms[m]      = ms_decay*ms[m] + (1 - ms_decay)*(g*g)
  *                         local_w[m] = w - local_lr*((g + r) + ((g*g)*(w - u_old))*(lambda/sqrt(ms[m] + epsilon)))
+ *   ODSGD_LOCAL_SGD_MOMENTUM  lv[m]  = local_momentum*lv[m] - local_lr*(g + r)
+ *                         local_w[m] = w + lv[m]
+ *     (Section 4.2 runs the local SGD updater with the server's learning rate
+ *     and momentum; read as a per-worker local velocity.  local_momentum = 0
+ *     gives exactly ODSGD_LOCAL_SGD.)
  * r = weight_decay*w; sqrt and divide are correctly rounded.  For the two
  * delay-compensated rules local_w[m] is read before it is overwritten, so it
  * must be initialised (to the weights the first gradients were taken at).
- * mean_square: host array [W] of host arrays [K] of device pointers to the
- * per-worker MeanSquare state (numel[k] floats each, 16-byte aligned, read and
- * written, caller-owned, zero for a fresh run); required for DCASGD_A, ignored
- * otherwise.  The pointers are uploaded on `stream`; the call returns after the
- * upload.  The paper gives lambda = 0.04 (c), lambda = 2 with ms_decay 0.95 or 0
- * (a) and never states epsilon.
+ * state: host array [W] of host arrays [K] of device pointers to the per-worker
+ * state (MeanSquare for DCASGD_A, local velocity lv for SGD_MOMENTUM; numel[k]
+ * floats each, 16-byte aligned, read and written, caller-owned, zero for a
+ * fresh run); required for those two rules, ignored otherwise.  A new
+ * registration replaces the previous one.  The pointers are uploaded on
+ * `stream`; the call returns after the upload.  The paper gives lambda = 0.04
+ * (c), lambda = 2 with ms_decay 0.95 or 0 (a) and never states epsilon.
  */
 #define ODSGD_LOCAL_SGD 0
 #define ODSGD_LOCAL_DCASGD_C 1
 #define ODSGD_LOCAL_DCASGD_A 2
+#define ODSGD_LOCAL_SGD_MOMENTUM 3
 typedef struct {
     int rule;
-    float lambda;
-    float ms_decay;
-    float epsilon;
+    float lambda;         /* DCASGD_C, DCASGD_A */
+    float ms_decay;       /* DCASGD_A */
+    float epsilon;        /* DCASGD_A */
+    float local_momentum; /* SGD_MOMENTUM */
 } odsgd_local_rule;
 int odsgd_set_local_rule(odsgd_handle *h, const odsgd_local_rule *rule,
-                         float *const *const *mean_square, void *stream);
+                         float *const *const *state, void *stream);
 
 /*
  * Warm-up length wp >= 0 (Alg. 2 input): iterations 0..wp-1 are synchronous SGD,

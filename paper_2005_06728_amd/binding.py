@@ -23,6 +23,7 @@ ODSGD_MAX_WORKERS = 64
 ODSGD_LOCAL_SGD = 0
 ODSGD_LOCAL_DCASGD_C = 1
 ODSGD_LOCAL_DCASGD_A = 2
+ODSGD_LOCAL_SGD_MOMENTUM = 3
 
 
 class odsgd_hyper(ctypes.Structure):
@@ -33,7 +34,8 @@ class odsgd_hyper(ctypes.Structure):
 
 class odsgd_local_rule(ctypes.Structure):
     _fields_ = [("rule", ctypes.c_int), ("lambda_", ctypes.c_float),
-                ("ms_decay", ctypes.c_float), ("epsilon", ctypes.c_float)]
+                ("ms_decay", ctypes.c_float), ("epsilon", ctypes.c_float),
+                ("local_momentum", ctypes.c_float)]
 
 
 class OdsgdError(RuntimeError):
@@ -167,11 +169,11 @@ def odsgd_ssgd_step(handle, hyper, stream=None):
           lib().odsgd_ssgd_step(handle, ctypes.byref(_hyper(hyper)), _stream(stream)))
 
 
-def odsgd_set_local_rule(handle, rule, lam=0.0, ms_decay=0.0, epsilon=0.0, mean_square_ptrs=None,
-                         stream=None):
-    """rule: ODSGD_LOCAL_*; mean_square_ptrs: [W][K] integers (DCASGD_A only)."""
-    r = odsgd_local_rule(int(rule), float(lam), float(ms_decay), float(epsilon))
-    top, keep = (None, None) if mean_square_ptrs is None else _ptr_rows(mean_square_ptrs)
+def odsgd_set_local_rule(handle, rule, lam=0.0, ms_decay=0.0, epsilon=0.0, state_ptrs=None,
+                         stream=None, local_momentum=0.0):
+    """rule: ODSGD_LOCAL_*; state_ptrs: [W][K] integers (DCASGD_A: MeanSquare, SGD_MOMENTUM: velocity)."""
+    r = odsgd_local_rule(int(rule), float(lam), float(ms_decay), float(epsilon), float(local_momentum))
+    top, keep = (None, None) if state_ptrs is None else _ptr_rows(state_ptrs)
     rc = lib().odsgd_set_local_rule(handle, ctypes.byref(r),
                                     None if top is None else ctypes.cast(top, ctypes.c_void_p),
                                     _stream(stream))
@@ -225,11 +227,14 @@ class Engine:
         if warmup_steps:
             odsgd_set_warmup(self.handle, warmup_steps)
 
-    def set_local_rule(self, rule, lam=0.0, ms_decay=0.0, epsilon=0.0, mean_square=None, stream=None):
-        """mean_square: [W][K] fp32 CUDA tensors holding the MeanSquare state (DCASGD_A)."""
-        self.mean_square = mean_square
-        ptrs = None if mean_square is None else [[t.data_ptr() for t in r] for r in mean_square]
-        odsgd_set_local_rule(self.handle, rule, lam, ms_decay, epsilon, ptrs, stream)
+    def set_local_rule(self, rule, lam=0.0, ms_decay=0.0, epsilon=0.0, mean_square=None, stream=None,
+                       local_momentum=0.0, local_velocity=None):
+        """mean_square / local_velocity: [W][K] fp32 CUDA tensors holding the per-worker
+        state of DCASGD_A / SGD_MOMENTUM."""
+        state = mean_square if mean_square is not None else local_velocity
+        self.local_state = state
+        ptrs = None if state is None else [[t.data_ptr() for t in r] for r in state]
+        odsgd_set_local_rule(self.handle, rule, lam, ms_decay, epsilon, ptrs, stream, local_momentum)
 
     def step(self, hyper, stream=None):
         odsgd_step(self.handle, hyper, stream)

@@ -97,6 +97,7 @@ enum Rule : int {
     RULE_SGD = 0,  // u_m = w - local_lr*(g_m + r)
     RULE_DCC = 1,  // + lambda * g_m*g_m*(w - u_m_old)                         (eq. DC-ASGD-c)
     RULE_DCA = 2,  // + lambda/sqrt(MeanSquare_m + eps) * g_m*g_m*(w - u_m_old) (eq. DC-ASGD-a)
+    RULE_MOM = 3,  // lv_m = mu_l*lv_m - local_lr*(g_m + r); u_m = w + lv_m    (local momentum SGD)
 };
 
 struct KernelArgs {
@@ -107,7 +108,7 @@ struct KernelArgs {
     int wfirst;  // first worker this launch touches
     int wcount;  // number of workers this launch touches (== W_T when W_T > 0)
     float lr, local_lr, momentum, weight_decay, grad_scale;
-    float lambda, ms_decay, one_minus_ms_decay, epsilon;
+    float lambda, ms_decay, one_minus_ms_decay, epsilon, local_momentum;
 };
 
 // chunk descriptor, 16 bytes: {tensor | vec<<31, count, offset_lo, offset_hi}
@@ -145,7 +146,7 @@ __device__ __forceinline__ void store(uint64_t base, unsigned idx, T x)
 // ---------------------------------------------------------------------------
 struct Hyp {
     float lr, local_lr, momentum, weight_decay, grad_scale;
-    float lambda, ms_decay, one_minus_ms_decay, epsilon;
+    float lambda, ms_decay, one_minus_ms_decay, epsilon, local_momentum;
 };
 
 __device__ __forceinline__ float sqrt_rn(float x) { return __builtin_sqrtf(x); }
@@ -161,6 +162,17 @@ __device__ __forceinline__ T update_local(T w0, T g, T r, float local_lr)
     T dm = g + r;
     T pm = local_lr * dm;
     return w0 - pm;
+}
+
+// local momentum SGD: lv' = mu_l * lv - local_lr * (g + r);  u = w + lv'
+template <typename T>
+__device__ __forceinline__ T update_local_momentum(T w0, T g, T r, T lv0, const Hyp &h, T &lv1)
+{
+    T dm = g + r;
+    T am = h.local_momentum * lv0;
+    T pm = h.local_lr * dm;
+    lv1 = am - pm;
+    return w0 + lv1;
 }
 
 // delay-compensated local updaters; u_old = the weights g was evaluated at.
@@ -221,8 +233,8 @@ __device__ __forceinline__ void apply_fixed(const Ptrs<W_T> &p, unsigned i, cons
     constexpr bool need_v = (MODE != MODE_LOCAL);
     constexpr bool need_u = (MODE != MODE_GLOBAL);
     constexpr bool local_rule = (MODE == MODE_OD || MODE == MODE_LOCAL);
-    constexpr bool need_u_old = local_rule && RULE != RULE_SGD;
-    constexpr bool need_ms = local_rule && RULE == RULE_DCA;
+    constexpr bool need_u_old = local_rule && (RULE == RULE_DCC || RULE == RULE_DCA);
+    constexpr bool need_ms = local_rule && (RULE == RULE_DCA || RULE == RULE_MOM);  // per-worker state
 
     T w0, v0, g[W_T], u_old[W_T], ms_old[W_T];
     w0 = load<ODSGD_NT_STATE_LD, T>(p.w, i);
@@ -262,12 +274,16 @@ __device__ __forceinline__ void apply_fixed(const Ptrs<W_T> &p, unsigned i, cons
             } else if constexpr (RULE == RULE_DCC) {
                 T gg = g[m] * g[m];
                 um = update_local_dc(w0, g[m], gg, u_old[m], r, h.lambda, h.local_lr);
-            } else {
+            } else if constexpr (RULE == RULE_DCA) {
                 T gg = g[m] * g[m];
                 T ms_new;
                 T lam = mean_square_step(gg, ms_old[m], h, ms_new);
                 store<ODSGD_NT_LOCAL, T>(p.ms[m], i, ms_new);
                 um = update_local_dc(w0, g[m], gg, u_old[m], r, lam, h.local_lr);
+            } else {
+                T lv1;
+                um = update_local_momentum(w0, g[m], r, ms_old[m], h, lv1);
+                store<ODSGD_NT_LOCAL, T>(p.ms[m], i, lv1);
             }
             store<ODSGD_NT_LOCAL, T>(p.u[m], i, um);
         }
@@ -300,7 +316,7 @@ __device__ __forceinline__ void apply_generic(ptr_table_t row, uint64_t byte_off
                 T u_old = load<ODSGD_NT_LOCAL, T>(pu, i);
                 T gg = gm * gm;
                 um = update_local_dc(w0, gm, gg, u_old, r, h.lambda, h.local_lr);
-            } else {
+            } else if constexpr (RULE == RULE_DCA) {
                 const uint64_t pms = row[2 + 2 * wtot + wfirst + m] + byte_off;
                 T u_old = load<ODSGD_NT_LOCAL, T>(pu, i);
                 T ms_old = load<ODSGD_NT_LOCAL, T>(pms, i);
@@ -309,6 +325,12 @@ __device__ __forceinline__ void apply_generic(ptr_table_t row, uint64_t byte_off
                 T lam = mean_square_step(gg, ms_old, h, ms_new);
                 store<ODSGD_NT_LOCAL, T>(pms, i, ms_new);
                 um = update_local_dc(w0, gm, gg, u_old, r, lam, h.local_lr);
+            } else {
+                const uint64_t plv = row[2 + 2 * wtot + wfirst + m] + byte_off;
+                T lv0 = load<ODSGD_NT_LOCAL, T>(plv, i);
+                T lv1;
+                um = update_local_momentum(w0, gm, r, lv0, h, lv1);
+                store<ODSGD_NT_LOCAL, T>(plv, i, lv1);
             }
             store<ODSGD_NT_LOCAL, T>(pu, i, um);
         }
@@ -336,7 +358,7 @@ __global__ void __launch_bounds__(kBlock) odsgd_kernel(KernelArgs a)
     const chunk_table_t chunks = (chunk_table_t)a.chunks;
     const ptr_table_t ptrs = (ptr_table_t)a.ptrs;
     const Hyp h{a.lr, a.local_lr, a.momentum, a.weight_decay, a.grad_scale,
-                a.lambda, a.ms_decay, a.one_minus_ms_decay, a.epsilon};
+                a.lambda, a.ms_decay, a.one_minus_ms_decay, a.epsilon, a.local_momentum};
     const unsigned tid = threadIdx.x;
     const int stride = 2 + 3 * a.wtot;
 
@@ -361,7 +383,7 @@ __global__ void __launch_bounds__(kBlock) odsgd_kernel(KernelArgs a)
             for (int m = 0; m < W_T; ++m) {
                 p.g[m] = row[2 + a.wfirst + m] + byte_off;
                 p.u[m] = row[2 + a.wtot + a.wfirst + m] + byte_off;
-                if constexpr (RULE == RULE_DCA)
+                if constexpr (RULE == RULE_DCA || RULE == RULE_MOM)
                     p.ms[m] = row[2 + 2 * a.wtot + a.wfirst + m] + byte_off;
             }
             for (unsigned i = tid; i < nvec; i += kBlock)
@@ -508,6 +530,7 @@ KernelFn pick_by_rule(int rule, int wcount)
     switch (rule) {
     case RULE_DCC: return pick_by_workers<MODE, RULE_DCC>(wcount);
     case RULE_DCA: return pick_by_workers<MODE, RULE_DCA>(wcount);
+    case RULE_MOM: return pick_by_workers<MODE, RULE_MOM>(wcount);
     default: return pick_by_workers<MODE, RULE_SGD>(wcount);
     }
 }
@@ -539,6 +562,7 @@ struct odsgd_handle {
     odsgd_local_rule rule;               // local updater of MODE_OD / MODE_LOCAL
     std::vector<int64_t> numel;
     std::vector<Range> ranges;           // every registered buffer, for alias checks of later registrations
+    size_t base_ranges;                  // how many of them odsgd_init registered
     std::vector<unsigned char> staging;  // host image of the tables (kept alive for the upload)
 };
 
@@ -558,10 +582,11 @@ size_t occupancy_cap_lds_bytes(const odsgd_handle *h, int mode, int wcount)
         int loads = (mode == MODE_LOCAL) ? wcount + 1 : wcount + 2;
         int stores = (mode == MODE_GLOBAL) ? 2 : (mode == MODE_LOCAL) ? wcount : wcount + 2;
         if (mode == MODE_OD || mode == MODE_LOCAL) {
-            if (h->rule.rule != ODSGD_LOCAL_SGD)
+            const int rl = h->rule.rule;
+            if (rl == ODSGD_LOCAL_DCASGD_C || rl == ODSGD_LOCAL_DCASGD_A)
                 loads += wcount;  // previous local weights
-            if (h->rule.rule == ODSGD_LOCAL_DCASGD_A) {
-                loads += wcount;  // MeanSquare state in ...
+            if (rl == ODSGD_LOCAL_DCASGD_A || rl == ODSGD_LOCAL_SGD_MOMENTUM) {
+                loads += wcount;  // per-worker state in ...
                 stores += wcount; // ... and out
             }
         }
@@ -607,6 +632,7 @@ int launch(odsgd_handle *h, int mode, int wfirst, int wcount, const odsgd_hyper 
     a.ms_decay = h->rule.ms_decay;
     a.one_minus_ms_decay = 1.0f - h->rule.ms_decay;
     a.epsilon = h->rule.epsilon;
+    a.local_momentum = h->rule.local_momentum;
 
     // one workgroup per chunk; beyond 2^25 workgroups (2^31 threads, the launch
     // limit is 2^32) the kernel's grid-stride loop takes over
@@ -722,9 +748,10 @@ int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel, float 
     h->tuning = tuning;
     h->iteration = 0;
     h->warmup_steps = 0;
-    h->rule = odsgd_local_rule{ODSGD_LOCAL_SGD, 0.0f, 0.0f, 0.0f};
+    h->rule = odsgd_local_rule{ODSGD_LOCAL_SGD, 0.0f, 0.0f, 0.0f, 0.0f};
     h->numel.assign(numel, numel + num_tensors);
     h->ranges = std::move(ranges);
+    h->base_ranges = h->ranges.size();
     h->d_ptrs = workspace;
     h->d_chunks = (const unsigned char *)workspace + ptr_bytes;
 
@@ -842,19 +869,22 @@ int odsgd_step(odsgd_handle *h, const odsgd_hyper *hyper, void *stream)
     return rc;
 }
 
-int odsgd_set_local_rule(odsgd_handle *h, const odsgd_local_rule *rule, float *const *const *mean_square,
+int odsgd_set_local_rule(odsgd_handle *h, const odsgd_local_rule *rule, float *const *const *state,
                          void *stream)
 {
     if (!h || !rule)
         return ODSGD_EINVAL;
-    if (rule->rule != ODSGD_LOCAL_SGD && rule->rule != ODSGD_LOCAL_DCASGD_C && rule->rule != ODSGD_LOCAL_DCASGD_A)
+    if (rule->rule != ODSGD_LOCAL_SGD && rule->rule != ODSGD_LOCAL_DCASGD_C &&
+        rule->rule != ODSGD_LOCAL_DCASGD_A && rule->rule != ODSGD_LOCAL_SGD_MOMENTUM)
         return ODSGD_EINVAL;
-    if (rule->rule == ODSGD_LOCAL_DCASGD_A) {
+    if (rule->rule == ODSGD_LOCAL_DCASGD_A || rule->rule == ODSGD_LOCAL_SGD_MOMENTUM) {
+        float *const *const *mean_square = state;
         if (!mean_square)
             return ODSGD_EINVAL;
         const int W = h->num_workers, K = h->num_tensors;
         const int stride = 2 + 3 * W;
-        std::vector<Range> all = h->ranges;
+        // a state registration replaces the previous one (its ranges were appended last)
+        std::vector<Range> all(h->ranges.begin(), h->ranges.begin() + (std::ptrdiff_t)h->base_ranges);
         std::vector<uint64_t> cols((size_t)K * W, 0);
         for (int m = 0; m < W; ++m) {
             if (!mean_square[m])

@@ -1,5 +1,5 @@
-"""GPU parity for the delay-compensated local updaters (DC-ASGD-c / DC-ASGD-a):
-HIP path through the C ABI against the CPU oracle, element by element."""
+"""GPU parity for the other local updaters (DC-ASGD-c, DC-ASGD-a, local momentum
+SGD): HIP path through the C ABI against the CPU oracle, element by element."""
 import numpy as np
 import pytest
 import torch
@@ -17,6 +17,19 @@ DEV = "cuda:0"
 # values the paper runs with (Section 4.3 / 4.4); epsilon is never stated there
 LAMBDA_C = 0.04
 LAMBDA_A, DECAY_A, EPS_A = 2.0, 0.95, 1e-7
+LOCAL_MOMENTUM = 0.9
+
+
+def install_rule(eng, rule, state, state_host):
+    """Set the local updater on the engine; return the matching oracle rule tuple."""
+    if rule == "c":
+        eng.set_local_rule(B.ODSGD_LOCAL_DCASGD_C, lam=LAMBDA_C)
+        return ("dcasgd_c", f32(LAMBDA_C))
+    if rule == "a":
+        eng.set_local_rule(B.ODSGD_LOCAL_DCASGD_A, lam=LAMBDA_A, ms_decay=DECAY_A, epsilon=EPS_A, mean_square=state)
+        return ("dcasgd_a", f32(LAMBDA_A), f32(DECAY_A), f32(EPS_A), state_host)
+    eng.set_local_rule(B.ODSGD_LOCAL_SGD_MOMENTUM, local_momentum=LOCAL_MOMENTUM, local_velocity=state)
+    return ("momentum", f32(LOCAL_MOMENTUM), state_host)
 
 
 def compare_ms(ms_dev, ms_host):
@@ -56,7 +69,7 @@ def test_hand_expanded_literals_on_gpu(golden_dcasgd):
     eng.close()
 
 
-@pytest.mark.parametrize("rule", ["c", "a"])
+@pytest.mark.parametrize("rule", ["c", "a", "m"])
 @pytest.mark.parametrize("W", [1, 3, 4, 8, 12, 16])
 def test_rules_ragged_sizes_schedule_and_split_calls(rule, W):
     say("rule=%s W=%d" % (rule, W))
@@ -75,12 +88,7 @@ def test_rules_ragged_sizes_schedule_and_split_calls(rule, W):
     eng = make_engine(st, warmup_steps=wp)
     hy = (0.05, 0.02, 0.9, 1e-3, 0.0)
     oh = oracle_hyper(hy)
-    if rule == "c":
-        eng.set_local_rule(B.ODSGD_LOCAL_DCASGD_C, lam=LAMBDA_C)
-        orule = ("dcasgd_c", f32(LAMBDA_C))
-    else:
-        eng.set_local_rule(B.ODSGD_LOCAL_DCASGD_A, lam=LAMBDA_A, ms_decay=DECAY_A, epsilon=EPS_A, mean_square=ms)
-        orule = ("dcasgd_a", f32(LAMBDA_A), f32(DECAY_A), f32(EPS_A), ms_h)
+    orule = install_rule(eng, rule, ms, ms_h)
     for it in range(5):                      # two warm-up iterations, then fused one-step-delay iterations
         eng.step(hy)
         oracle.step(it, wp, hs["w"], hs["v"], hs["g"], hs["u"], rule=orule, **oh)
@@ -104,24 +112,19 @@ def test_rules_ragged_sizes_schedule_and_split_calls(rule, W):
     eng.close()
 
 
-@pytest.mark.parametrize("name,rule,iters", [("resnet20", "c", 20), ("resnet20", "a", 20),
-                                             ("resnet50", "a", 2), ("vgg16", "c", 1)])
+@pytest.mark.parametrize("name,rule,iters", [("resnet20", "c", 20), ("resnet20", "a", 20), ("lenet5", "m", 10),
+                                             ("resnet50", "a", 2), ("resnet50", "m", 2), ("vgg16", "c", 1)])
 def test_workloads_with_rules(name, rule, iters):
     w = wl.WORKLOADS[name]
     say("workload %s rule %s iterations %d" % (name, rule, iters))
     st = wl.allocate(w, DEV)
-    ms = [[torch.zeros_like(t) for t in st["w"]] for _ in range(w.num_workers)] if rule == "a" else None
+    ms = [[torch.zeros_like(t) for t in st["w"]] for _ in range(w.num_workers)] if rule in "am" else None
     hs = host_state(st)
     ms_h = [to_host(r) for r in ms] if ms else None
     eng = make_engine(st, warmup_steps=1)
     hy = hyper_tuple(w.hyper)
     oh = oracle_hyper(hy)
-    if rule == "c":
-        eng.set_local_rule(B.ODSGD_LOCAL_DCASGD_C, lam=LAMBDA_C)
-        orule = ("dcasgd_c", f32(LAMBDA_C))
-    else:
-        eng.set_local_rule(B.ODSGD_LOCAL_DCASGD_A, lam=LAMBDA_A, ms_decay=DECAY_A, epsilon=EPS_A, mean_square=ms)
-        orule = ("dcasgd_a", f32(LAMBDA_A), f32(DECAY_A), f32(EPS_A), ms_h)
+    orule = install_rule(eng, rule, ms, ms_h)
     for it in range(iters + 1):
         wl.fill_all_grads_(st, w, it)
         refresh_host_grads(st, hs)
@@ -161,6 +164,11 @@ def test_rule_error_paths():
     eng.step((0.1, 0.1, 0.9, 0.0, 0.0))
     eng.set_local_rule(B.ODSGD_LOCAL_SGD)
     eng.step((0.1, 0.1, 0.9, 0.0, 0.0))
+    with pytest.raises(B.OdsgdError) as e:
+        eng.set_local_rule(B.ODSGD_LOCAL_SGD_MOMENTUM, local_momentum=0.9)   # state missing
+    assert e.value.code == B.ODSGD_EINVAL
+    eng.set_local_rule(B.ODSGD_LOCAL_SGD_MOMENTUM, local_momentum=0.9, local_velocity=[[t()], [t()]])
+    eng.step((0.1, 0.1, 0.9, 0.0, 0.0))
     torch.cuda.synchronize()
-    assert eng.iteration == 3
+    assert eng.iteration == 4
     eng.close()
