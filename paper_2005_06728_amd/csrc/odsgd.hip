@@ -3,7 +3,7 @@
 // One launch covers every parameter tensor ("multi-tensor apply"): odsgd_init
 // cuts the K tensors into fixed-size chunks and writes, into caller-provided
 // device memory, a chunk table (which tensor, where, how many elements) and a
-// pointer table (2 + 2W device pointers per tensor).  A workgroup is a single
+// pointer table (2 + 3W device pointers per tensor).  A workgroup is a single
 // wavefront; it takes one chunk, fetches its descriptor and pointers with scalar
 // loads, and streams the chunk with 128-bit loads and stores (by default a chunk
 // is 256 elements: one 16-byte access per lane, 1 KiB per wavefront, per array).
@@ -12,8 +12,8 @@
 // staging and no matrix-core use.
 //
 // Launch shape.  With 2W + 4 concurrent streams (W = 8: 20, W = 16: 36) the
-// memory system delivers the most when few, small requests windows are in
-// flight: measured on MI355X, one-wavefront workgroups taking consecutive
+// memory system delivers the most when few requests are in flight and the
+// whole chip walks one narrow window of each array: measured on MI355X, one-wavefront workgroups taking consecutive
 // 1 KiB tiles in dispatch order, with only about 3-4 wavefronts resident per
 // CU, sustain 6.0-6.3 TB/s, against 5.2-5.4 TB/s for the same kernel at full
 // occupancy or as a persistent grid.  Residency is capped by requesting (and
@@ -99,6 +99,10 @@ enum Rule : int {
     RULE_DCA = 2,  // + lambda/sqrt(MeanSquare_m + eps) * g_m*g_m*(w - u_m_old) (eq. DC-ASGD-a)
     RULE_MOM = 3,  // lv_m = mu_l*lv_m - local_lr*(g_m + r); u_m = w + lv_m    (local momentum SGD)
 };
+
+static_assert(RULE_SGD == ODSGD_LOCAL_SGD && RULE_DCC == ODSGD_LOCAL_DCASGD_C &&
+                  RULE_DCA == ODSGD_LOCAL_DCASGD_A && RULE_MOM == ODSGD_LOCAL_SGD_MOMENTUM,
+              "kernel rule ids are the public ones");
 
 struct KernelArgs {
     const void *chunks;  // device: nchunks * 16 bytes
@@ -362,11 +366,14 @@ __global__ void __launch_bounds__(kBlock) odsgd_kernel(KernelArgs a)
     const unsigned tid = threadIdx.x;
     const int stride = 2 + 3 * a.wtot;
 
-    // Workgroup b takes chunk b.  The dispatcher hands consecutive workgroups to
-    // the 8 XCDs in turn, so at any moment the chip works on one narrow, sliding
-    // window of each array; giving every XCD a contiguous range of its own
-    // instead was measured 15 % slower.
-    for (unsigned c = blockIdx.x; c < (unsigned)a.nchunks; c += gridDim.x) {
+    // Workgroup b takes chunk b (the host never launches more workgroups than
+    // chunks, so the first trip needs no bounds check and the descriptor fetch can
+    // be issued together with the kernel arguments).  The dispatcher hands
+    // consecutive workgroups to the 8 XCDs in turn, so at any moment the chip works
+    // on one narrow, sliding window of each array; giving every XCD a contiguous
+    // range of its own instead was measured 15 % slower.
+    unsigned c = blockIdx.x;
+    do {
         const u4 d = chunks[c];
         const uint32_t tensor = d.x & ~kVecFlag;
         const bool vec = (d.x & kVecFlag) != 0;
@@ -376,15 +383,33 @@ __global__ void __launch_bounds__(kBlock) odsgd_kernel(KernelArgs a)
         const unsigned nvec = vec ? (count >> 2) : 0u;
 
         if constexpr (W_T > 0) {
+            // Fetch the whole pointer row before touching any of it: the scalar loads
+            // are then in flight together instead of one memory latency after another
+            // (with 3-4 wavefronts per CU that latency is not hidden by anyone else).
+            constexpr bool with_state = (RULE == RULE_DCA || RULE == RULE_MOM);
+            uint64_t raw_wv[2], raw_g[W_T], raw_u[W_T], raw_s[W_T];
+            raw_wv[0] = row[0];
+            raw_wv[1] = row[1];
+#pragma unroll
+            for (int m = 0; m < W_T; ++m)
+                raw_g[m] = row[2 + a.wfirst + m];
+#pragma unroll
+            for (int m = 0; m < W_T; ++m)
+                raw_u[m] = row[2 + a.wtot + a.wfirst + m];
+            if constexpr (with_state) {
+#pragma unroll
+                for (int m = 0; m < W_T; ++m)
+                    raw_s[m] = row[2 + 2 * a.wtot + a.wfirst + m];
+            }
             Ptrs<W_T> p;
-            p.w = row[0] + byte_off;
-            p.v = row[1] + byte_off;
+            p.w = raw_wv[0] + byte_off;
+            p.v = raw_wv[1] + byte_off;
 #pragma unroll
             for (int m = 0; m < W_T; ++m) {
-                p.g[m] = row[2 + a.wfirst + m] + byte_off;
-                p.u[m] = row[2 + a.wtot + a.wfirst + m] + byte_off;
-                if constexpr (RULE == RULE_DCA || RULE == RULE_MOM)
-                    p.ms[m] = row[2 + 2 * a.wtot + a.wfirst + m] + byte_off;
+                p.g[m] = raw_g[m] + byte_off;
+                p.u[m] = raw_u[m] + byte_off;
+                if constexpr (with_state)
+                    p.ms[m] = raw_s[m] + byte_off;
             }
             for (unsigned i = tid; i < nvec; i += kBlock)
                 apply_fixed<W_T, MODE, RULE, f4>(p, i, h);
@@ -396,7 +421,8 @@ __global__ void __launch_bounds__(kBlock) odsgd_kernel(KernelArgs a)
             for (unsigned t = nvec * 4 + tid; t < count; t += kBlock)
                 apply_generic<MODE, RULE, float>(row, byte_off, a.wtot, a.wfirst, a.wcount, t, h);
         }
-    }
+        c += gridDim.x;
+    } while (c < (unsigned)a.nchunks);
 }
 
 // Plain copy, one 1 KiB tile per wavefront: a kernel of exactly known traffic

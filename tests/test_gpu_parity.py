@@ -397,3 +397,40 @@ def test_non_default_stream():
         oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], **oracle_hyper(hy))
     assert compare(st, hs)[0] == 0
     eng.close()
+
+
+def test_hip_graph_replay_matches_eager():
+    """The step is a single kernel launch and nothing else, so it can be captured.
+    Replay the graph several times with eager work and synchronisation in between
+    and compare every replay with the oracle (the iteration counter is host state
+    and advances at capture time only, so the schedule must not change mid-graph)."""
+    w = wl.WORKLOADS["resnet20"]
+    st = wl.allocate(w, DEV)
+    hs = host_state(st)
+    eng = make_engine(st)
+    hy = hyper_tuple(w.hyper)
+    oh = oracle_hyper(hy)
+    wl.fill_all_grads_(st, w, 0)
+    refresh_host_grads(st, hs)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for _ in range(3):
+            eng.step(hy, side)
+    torch.cuda.synchronize()
+    steps_done = 0
+    for rep in range(4):
+        graph.replay()
+        torch.cuda.synchronize()
+        for _ in range(3):
+            oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], **oh)
+        steps_done += 3
+        assert compare(st, hs, label="replay %d" % rep)[0] == 0
+        # eager work between replays: new gradients, one eager step
+        wl.fill_all_grads_(st, w, rep + 1)
+        refresh_host_grads(st, hs)
+        eng.step(hy)
+        oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], **oh)
+        assert compare(st, hs, label="eager after replay %d" % rep)[0] == 0
+    eng.close()
