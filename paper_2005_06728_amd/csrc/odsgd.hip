@@ -49,7 +49,11 @@ namespace {
 #define ODSGD_NT_LOCAL 1  // local weights are written once: non-temporal stores
 #endif
 #ifndef ODSGD_NT_STATE_LD
-#define ODSGD_NT_STATE_LD 1  // w, momentum loads: next touched one whole step later
+// w and momentum are the only arrays read again by the next step.  Loading them
+// with ordinary (cacheable) loads while everything else streams non-temporally
+// is 4 % faster even with a cold cache, and lets them stay in the 256 MB
+// last-level cache from one step to the next when they fit (ResNet-50: 204 MB).
+#define ODSGD_NT_STATE_LD 0
 #endif
 #ifndef ODSGD_NT_STATE_ST
 #define ODSGD_NT_STATE_ST 1  // w, momentum stores
@@ -57,8 +61,8 @@ namespace {
 #define ODSGD_BLOCK 64  // one wavefront per workgroup
 #ifndef ODSGD_INFLIGHT_MEMOPS_PER_CU
 // target of (resident wavefronts per CU) x (128-bit loads + stores per lane per
-// tile); measured optimum 80-96 for every entry point and worker count tried
-#define ODSGD_INFLIGHT_MEMOPS_PER_CU 88
+// tile); measured optimum 100-120 for every entry point and worker count tried
+#define ODSGD_INFLIGHT_MEMOPS_PER_CU 110
 #endif
 
 constexpr int kBlock = ODSGD_BLOCK;
@@ -617,9 +621,7 @@ size_t occupancy_cap_lds_bytes(const odsgd_handle *h, int mode, int wcount)
             }
         }
         const int ops = loads + stores;
-        // nearest integer; rounded up once a tile spans many arrays
-        waves = (ops < 24) ? (ODSGD_INFLIGHT_MEMOPS_PER_CU + ops / 2) / ops
-                           : (ODSGD_INFLIGHT_MEMOPS_PER_CU + ops - 1) / ops;
+        waves = (ODSGD_INFLIGHT_MEMOPS_PER_CU + ops / 2) / ops;  // nearest integer
         // the adaptive rule spends a correctly rounded sqrt and divide per element and
         // worker: more wavefronts are needed to hide that arithmetic
         if ((mode == MODE_OD || mode == MODE_LOCAL) && h->rule.rule == ODSGD_LOCAL_DCASGD_A)
