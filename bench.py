@@ -25,7 +25,7 @@ HBM_PEAK_GBPS = 8000.0
 
 # HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs,
 # scaled by the same counters on the 1 GiB copy probe); see profiles/.  Absent = not measured.
-MEASURED_TRAFFIC_BYTES = {"resnet50": 2.0578e9, "vgg16": 1.9996e10}
+MEASURED_TRAFFIC_BYTES = {"resnet50": 2.0576e9, "vgg16": 1.9992e10}
 
 PAPER_CONTEXT = {
     "note": "the paper reports end-to-end training speed only, never the update path; other hardware, context only",
@@ -247,11 +247,14 @@ def main():
     ap.add_argument("--others", default="vgg16,alexnet",
                     help="comma list of further workloads measured in the same run ('' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-entry-points", action="store_true",
-                    help="skip the secondary measurements of the other entry points / local updaters")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="only the headline workload and the copy probe (what the rocprofv3 runs use): no "
+                         "other workloads, layouts, entry points, cold-cache or CPU measurements")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only the plain copy kernel of known traffic (counter calibration)")
     args = ap.parse_args()
+    if args.headline_only:
+        args.others, args.no_cpu_baseline = "", True
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the W workers are W gradient buffers in "
                  "one HBM); --gpus %d is not supported, no multi-GPU figure exists" % args.gpus)
@@ -274,8 +277,8 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(wl_mod, args.workload, st)
-    cold = None if args.no_entry_points else time_cold(wl_mod, B, torch, args.workload, st)
-    entry_points = {} if args.no_entry_points else time_entry_points(wl_mod, B, torch, args.workload, st)
+    cold = None if args.headline_only else time_cold(wl_mod, B, torch, args.workload, st)
+    entry_points = {} if args.headline_only else time_entry_points(wl_mod, B, torch, args.workload, st)
     del st
     torch.cuda.empty_cache()
 
@@ -290,14 +293,15 @@ def main():
     # the same fused step with every role packed into one flat bucket (the usual
     # gradient-bucket layout) instead of one allocation per tensor
     buckets = {}
-    for name in [args.workload] + [x for x in args.others.split(",") if x and x != args.workload]:
+    for name in ([] if args.headline_only else
+                 [args.workload] + [x for x in args.others.split(",") if x and x != args.workload]):
         r, st2 = time_gpu(wl_mod, B, torch, name, max(5, min(args.steps, 20)), args.warmup, layout="arena")
         del st2
         torch.cuda.empty_cache()
         s = summarize(r)
         buckets[name] = {k: s[k] for k in ("kernel_ms_mean", "hbm_gbps", "hbm_frac")}
 
-    small = {} if args.no_entry_points else {n: time_small(wl_mod, B, torch, n) for n in ("lenet5", "resnet20")}
+    small = {} if args.headline_only else {n: time_small(wl_mod, B, torch, n) for n in ("lenet5", "resnet20")}
     probe = time_copy_probe(B, torch, 20, 3)
     w = wl_mod.WORKLOADS[args.workload]
     line = {
