@@ -49,14 +49,22 @@ namespace {
 #define ODSGD_NT_LOCAL 1  // local weights are written once: non-temporal stores
 #endif
 #ifndef ODSGD_NT_STATE_LD
-// w and momentum are the only arrays read again by the next step.  Loading them
-// with ordinary (cacheable) loads while everything else streams non-temporally
-// is 4 % faster even with a cold cache, and lets them stay in the 256 MB
-// last-level cache from one step to the next when they fit (ResNet-50: 204 MB).
+// w and momentum are the only arrays the next step reads again.  Loading these
+// two with ordinary (cacheable) loads while everything else streams
+// non-temporally is 4 % faster even with a cold cache, and lets them stay in the
+// 256 MB last-level cache from one step to the next when they fit (ResNet-50:
+// 204 MB).  Caching even one gradient stream as well, by contrast, costs 10 %.
 #define ODSGD_NT_STATE_LD 0
 #endif
 #ifndef ODSGD_NT_STATE_ST
 #define ODSGD_NT_STATE_ST 1  // w, momentum stores
+#endif
+#ifndef ODSGD_NT_INPLACE_LD
+// per-worker arrays that a delay-compensated or momentum rule updates in place
+// (previous local weights, MeanSquare, local velocity): although they share the
+// read-then-write pattern of w and momentum, loading them through the cache was
+// measured 10 % slower, so they stream like the gradients
+#define ODSGD_NT_INPLACE_LD 1
 #endif
 #define ODSGD_BLOCK 64  // one wavefront per workgroup
 #ifndef ODSGD_INFLIGHT_MEMOPS_PER_CU
@@ -254,12 +262,12 @@ __device__ __forceinline__ void apply_fixed(const Ptrs<W_T> &p, unsigned i, cons
     if constexpr (need_u_old) {
 #pragma unroll
         for (int m = 0; m < W_T; ++m)
-            u_old[m] = load<ODSGD_NT_LOCAL, T>(p.u[m], i);
+            u_old[m] = load<ODSGD_NT_INPLACE_LD, T>(p.u[m], i);
     }
     if constexpr (need_ms) {
 #pragma unroll
         for (int m = 0; m < W_T; ++m)
-            ms_old[m] = load<ODSGD_NT_LOCAL, T>(p.ms[m], i);
+            ms_old[m] = load<ODSGD_NT_INPLACE_LD, T>(p.ms[m], i);
     }
 
     T r = h.weight_decay * w0;
@@ -321,13 +329,13 @@ __device__ __forceinline__ void apply_generic(ptr_table_t row, uint64_t byte_off
             if constexpr (RULE == RULE_SGD) {
                 um = update_local(w0, gm, r, h.local_lr);
             } else if constexpr (RULE == RULE_DCC) {
-                T u_old = load<ODSGD_NT_LOCAL, T>(pu, i);
+                T u_old = load<ODSGD_NT_INPLACE_LD, T>(pu, i);
                 T gg = gm * gm;
                 um = update_local_dc(w0, gm, gg, u_old, r, h.lambda, h.local_lr);
             } else if constexpr (RULE == RULE_DCA) {
                 const uint64_t pms = row[2 + 2 * wtot + wfirst + m] + byte_off;
-                T u_old = load<ODSGD_NT_LOCAL, T>(pu, i);
-                T ms_old = load<ODSGD_NT_LOCAL, T>(pms, i);
+                T u_old = load<ODSGD_NT_INPLACE_LD, T>(pu, i);
+                T ms_old = load<ODSGD_NT_INPLACE_LD, T>(pms, i);
                 T gg = gm * gm;
                 T ms_new;
                 T lam = mean_square_step(gg, ms_old, h, ms_new);
@@ -335,7 +343,7 @@ __device__ __forceinline__ void apply_generic(ptr_table_t row, uint64_t byte_off
                 um = update_local_dc(w0, gm, gg, u_old, r, lam, h.local_lr);
             } else {
                 const uint64_t plv = row[2 + 2 * wtot + wfirst + m] + byte_off;
-                T lv0 = load<ODSGD_NT_LOCAL, T>(plv, i);
+                T lv0 = load<ODSGD_NT_INPLACE_LD, T>(plv, i);
                 T lv1;
                 um = update_local_momentum(w0, gm, r, lv0, h, lv1);
                 store<ODSGD_NT_LOCAL, T>(plv, i, lv1);
