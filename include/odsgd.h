@@ -28,6 +28,12 @@
  * valid on the GPU that is current when odsgd_init is called.  Arrays named
  * "host" are read during the call only.
  *
+ * Tuning.  Launch shape is chosen per call from the worker count and entry
+ * point; three environment variables, read by odsgd_init, override it for
+ * experiments and never change results: ODSGD_CHUNK_ELEMS (elements per chunk,
+ * default 256), ODSGD_WAVES_PER_CU (resident wavefronts per compute unit; 0 =
+ * automatic, negative = uncapped), ODSGD_BLOCKS_PER_CU (> 0: persistent grid).
+ *
  * Execution model.  odsgd_local_update / odsgd_global_update / odsgd_step /
  * odsgd_ssgd_step enqueue one kernel on the given HIP stream and return
  * without synchronising.  A handle is not thread-safe; distinct handles are

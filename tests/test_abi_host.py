@@ -99,3 +99,18 @@ def test_calls_reject_null_handle():
     assert L.odsgd_ssgd_step(None, ctypes.byref(h), None) == B.ODSGD_EINVAL
     assert L.odsgd_destroy(None) == B.ODSGD_EINVAL
     assert L.odsgd_set_warmup(None, 1) == B.ODSGD_EINVAL
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 and as C++ without any HIP or torch type."""
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "odsgd.h"\n'
+                   'int main(void) { odsgd_hyper h = {0.1f, 0.1f, 0.9f, 0.0f, 0.0f};\n'
+                   '  odsgd_local_rule r = {ODSGD_LOCAL_SGD, 0.0f, 0.0f, 0.0f, 0.0f};\n'
+                   '  return (int)h.lr + r.rule + (odsgd_strerror == 0) + (odsgd_step == 0); }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, "-c", str(src),
+                    "-o", str(tmp_path / "c.o")], check=True)
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Wextra", "-Werror", "-I", inc, "-x", "c++", "-c", str(src),
+                    "-o", str(tmp_path / "cpp.o")], check=True)

@@ -434,3 +434,44 @@ def test_hip_graph_replay_matches_eager():
         oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], **oh)
         assert compare(st, hs, label="eager after replay %d" % rep)[0] == 0
     eng.close()
+
+
+def test_tensor_beyond_32_bit_element_offsets():
+    """One tensor of 2^32 + 70,003 elements (W = 1): chunk offsets need the high word
+    of the 64-bit element offset and byte offsets exceed 2^34.  Four arrays of 17 GB
+    each stay on the GPU; the oracle checks a sample: both ends, the region around
+    element 2^32, and a million random positions."""
+    n = (1 << 32) + 70003
+    free, _ = torch.cuda.mem_get_info()
+    if free < 5 * 4 * n:
+        pytest.skip("needs about 86 GB of free device memory")
+    say("huge tensor: n=%d" % n)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(77)
+    mk = lambda: torch.empty(n, dtype=torch.float32, device=DEV)
+    w, v, g, u = mk(), mk(), mk(), mk()
+    step = 1 << 28
+    for lo in range(0, n, step):
+        hi = min(n, lo + step)
+        w[lo:hi].normal_(0, 0.05, generator=gen)
+        v[lo:hi].normal_(0, 1e-3, generator=gen)
+        g[lo:hi].normal_(0, 1e-3, generator=gen)
+    u.fill_(CANARY)
+    idx = torch.cat([torch.arange(0, 5000, device=DEV), torch.arange(n - 5000, n, device=DEV),
+                     torch.arange((1 << 32) - 3000, (1 << 32) + 3000, device=DEV),
+                     torch.arange((1 << 31) - 1000, (1 << 31) + 1000, device=DEV),
+                     torch.randint(0, n, (1 << 20,), device=DEV, generator=gen)])
+    hw, hv, hg = (t[idx].cpu().numpy().copy() for t in (w, v, g))
+    hu = np.zeros_like(hw)
+    eng = B.Engine([w], [v], [[g]], [[u]])
+    hy = (0.05, 0.02, 0.9, 1e-3, 1.0)
+    eng.step(hy)
+    torch.cuda.synchronize()
+    oracle.od_step([hw], [hv], [[hg]], [[hu]], **oracle_hyper(hy))
+    assert same_bits(w[idx].cpu().numpy(), hw)
+    assert same_bits(v[idx].cpu().numpy(), hv)
+    assert same_bits(u[idx].cpu().numpy(), hu)
+    # every element was written exactly once: no canary left in the local weights
+    for lo in range(0, n, step):
+        assert not bool(torch.any(u[lo:min(n, lo + step)] == CANARY))
+    eng.close()
