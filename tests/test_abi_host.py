@@ -108,7 +108,8 @@ def test_header_is_plain_c(tmp_path):
     src.write_text('#include "odsgd.h"\n'
                    'int main(void) { odsgd_hyper h = {0.1f, 0.1f, 0.9f, 0.0f, 0.0f};\n'
                    '  odsgd_local_rule r = {ODSGD_LOCAL_SGD, 0.0f, 0.0f, 0.0f, 0.0f};\n'
-                   '  return (int)h.lr + r.rule + (odsgd_strerror == 0) + (odsgd_step == 0); }\n')
+                   '  int (*step)(odsgd_handle *, const odsgd_hyper *, void *) = odsgd_step;\n'
+                   '  return (int)h.lr + r.rule + (step != odsgd_ssgd_step ? 0 : 1); }\n')
     inc = os.path.join(ROOT, "include")
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, "-c", str(src),
                     "-o", str(tmp_path / "c.o")], check=True)
