@@ -116,7 +116,8 @@ int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel,
                void *stream);
 
 /*
- * Local update (Alg. 2, training stage): local_w[m] = w - local_lr*(grads[m] + wd*w)
+ * Local update (Alg. 2, training stage) with the local updater in force (default
+ * SGD: local_w[m] = w - local_lr*(grads[m] + wd*w); see odsgd_set_local_rule),
  * for worker m = `worker`, or for all workers if worker == -1.  Reads w as it is
  * when the kernel runs: for iteration t it must be enqueued BEFORE that
  * iteration's odsgd_global_update.  Uses hyper->local_lr and hyper->weight_decay.
@@ -138,7 +139,10 @@ int odsgd_global_update(odsgd_handle *h, const odsgd_hyper *hyper, void *stream)
  *             odsgd_local_update(h, -1, ...) followed by odsgd_global_update(h, ...)
  *   i <  wp : warm-up iteration        -- identical to odsgd_ssgd_step
  * Reads w, mom and the W gradients once and writes w, mom and the W local
- * weights once.  Advances the iteration counter by one.
+ * weights once.  Advances the iteration counter by one.  The call is a single
+ * kernel launch and may be captured into a HIP graph; the counter is host
+ * state, so which kind of iteration a captured launch performs is fixed at
+ * capture time.
  */
 int odsgd_step(odsgd_handle *h, const odsgd_hyper *hyper, void *stream);
 
