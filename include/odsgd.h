@@ -116,6 +116,23 @@ int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel,
                void *stream);
 
 /*
+ * Inspection aid: build, in host memory and without touching any device, the
+ * exact table image odsgd_init would upload for these arguments -- the pointer
+ * table (num_tensors rows of 2 + 3*num_workers 64-bit addresses:
+ * w, mom, grads[0..], local_w[0..], then the per-worker state columns, zero
+ * until a rule registers them) followed, at *chunk_table_offset, by
+ * *num_chunks chunk descriptors of four 32-bit words {tensor index | bit 31 set
+ * if the chunk takes 128-bit accesses, element count, element offset low,
+ * element offset high}.  The pointers are only inspected, never dereferenced.
+ * image must hold odsgd_workspace_bytes(...) bytes.  Same validation and error
+ * codes as odsgd_init.
+ */
+int odsgd_plan_host(int num_tensors, const int64_t *numel, float *const *w, float *const *mom,
+                    const float *const *const *grads, float *const *const *local_w,
+                    int num_workers, void *image, size_t image_bytes, int64_t *num_chunks,
+                    size_t *chunk_table_offset);
+
+/*
  * Local update (Alg. 2, training stage) with the local updater in force (default
  * SGD: local_w[m] = w - local_lr*(grads[m] + wd*w); see odsgd_set_local_rule),
  * for worker m = `worker`, or for all workers if worker == -1.  Reads w as it is

@@ -66,6 +66,9 @@ def lib():
     L.odsgd_init.restype = ctypes.c_int
     L.odsgd_init.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64p, vp, vp, vp, vp,
                              ctypes.c_int, vp, ctypes.c_size_t, vp]
+    L.odsgd_plan_host.restype = ctypes.c_int
+    L.odsgd_plan_host.argtypes = [ctypes.c_int, i64p, vp, vp, vp, vp, ctypes.c_int, vp, ctypes.c_size_t,
+                                  ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_size_t)]
     L.odsgd_local_update.restype = ctypes.c_int
     L.odsgd_local_update.argtypes = [vp, ctypes.c_int, hp, vp]
     for name in ("odsgd_global_update", "odsgd_step", "odsgd_ssgd_step"):
@@ -129,6 +132,36 @@ def odsgd_init(numel, w_ptrs, mom_ptrs, grad_ptrs, local_ptrs, num_workers,
     if rc != ODSGD_OK:
         raise OdsgdError(rc, "odsgd_init")
     return out.value
+
+
+def odsgd_plan_host(numel, w_ptrs, mom_ptrs, grad_ptrs, local_ptrs, num_workers):
+    """Host-only: the tables odsgd_init would upload.  Returns (pointer_rows, chunks)
+    with pointer_rows[k] = list of 2 + 3W addresses and chunks = list of
+    (tensor, vec, count, offset)."""
+    import struct
+    nbytes = odsgd_workspace_bytes(numel, num_workers)
+    if nbytes == 0:
+        raise OdsgdError(ODSGD_EINVAL, "odsgd_workspace_bytes")
+    buf = ctypes.create_string_buffer(nbytes)
+    g_top, g_keep = _ptr_rows(grad_ptrs)
+    u_top, u_keep = _ptr_rows(local_ptrs)
+    w_row, m_row, n_arr = _ptr_row(w_ptrs), _ptr_row(mom_ptrs), _i64_array(numel)
+    nch, off = ctypes.c_int64(), ctypes.c_size_t()
+    rc = lib().odsgd_plan_host(len(numel), n_arr, ctypes.cast(w_row, ctypes.c_void_p),
+                               ctypes.cast(m_row, ctypes.c_void_p), ctypes.cast(g_top, ctypes.c_void_p),
+                               ctypes.cast(u_top, ctypes.c_void_p), int(num_workers), buf, nbytes,
+                               ctypes.byref(nch), ctypes.byref(off))
+    del g_keep, u_keep
+    if rc != ODSGD_OK:
+        raise OdsgdError(rc, "odsgd_plan_host")
+    stride = 2 + 3 * num_workers
+    raw = buf.raw
+    rows = [list(struct.unpack_from("<%dQ" % stride, raw, k * stride * 8)) for k in range(len(numel))]
+    chunks = []
+    for c in range(nch.value):
+        t, cnt, lo, hi = struct.unpack_from("<4I", raw, off.value + 16 * c)
+        chunks.append((t & 0x7fffffff, bool(t >> 31), cnt, lo | (hi << 32)))
+    return rows, chunks
 
 
 def _hyper(h):

@@ -546,6 +546,119 @@ bool ranges_alias(std::vector<Range> &r)
     return false;
 }
 
+// The launch plan: host image of the two tables odsgd_init uploads, plus the
+// registered address ranges.  Building it touches no device.
+struct Plan {
+    Tuning tuning;
+    std::vector<unsigned char> image;  // [pointer table | chunk table], sized for the upper bound of chunks
+    size_t ptr_bytes;                  // offset of the chunk table inside image
+    int64_t nchunks;                   // chunks actually emitted
+    std::vector<Range> ranges;
+};
+
+int make_plan(Plan &plan, int num_tensors, const int64_t *numel, float *const *w, float *const *mom,
+              const float *const *const *grads, float *const *const *local_w, int num_workers)
+{
+    if (num_tensors < 1 || !numel || !w || !mom || !grads || !local_w || num_workers < 1 ||
+        num_workers > ODSGD_MAX_WORKERS)
+        return ODSGD_EINVAL;
+    for (int m = 0; m < num_workers; ++m)
+        if (!grads[m] || !local_w[m])
+            return ODSGD_EINVAL;
+
+    plan.tuning = current_tuning();
+    int err = 0;
+    const int64_t max_chunks = count_chunks(num_tensors, numel, plan.tuning.chunk_elems, &err);
+    if (max_chunks < 0)
+        return err;
+
+    const int W = num_workers;
+    const int stride = 2 + 3 * W;
+    const int registered = 2 + 2 * W;  // the per-worker state columns stay null until a rule registers them
+
+    // pointer checks: non-null and 4-byte aligned where the tensor is not empty
+    plan.ranges.clear();
+    plan.ranges.reserve((size_t)num_tensors * stride + 1);
+    std::vector<unsigned char> vec_ok(num_tensors, 1);
+    // elements before the first tile boundary, when every array of the tensor sits
+    // at the same offset from one (packed buckets); 0 = chunks start at element 0
+    std::vector<int64_t> head(num_tensors, 0);
+    for (int k = 0; k < num_tensors; ++k) {
+        if (numel[k] == 0)
+            continue;
+        const size_t bytes = (size_t)numel[k] * sizeof(float);
+        const uintptr_t phase = (uintptr_t)w[k] % kTileAlignBytes;
+        bool same_phase = true;
+        for (int j = 0; j < registered; ++j) {
+            const void *p = j == 0   ? (const void *)w[k]
+                            : j == 1 ? (const void *)mom[k]
+                            : j < 2 + W ? (const void *)grads[j - 2][k]
+                                        : (const void *)local_w[j - 2 - W][k];
+            if (!p)
+                return ODSGD_EINVAL;
+            const uintptr_t a = (uintptr_t)p;
+            if (a % 4 != 0)
+                return ODSGD_EALIGN;
+            if (a % 16 != 0)
+                vec_ok[k] = 0;
+            if (a % kTileAlignBytes != phase)
+                same_phase = false;
+            const bool is_output = (j < 2) || (j >= 2 + W);
+            plan.ranges.push_back(Range{a, a + bytes, is_output});
+        }
+        if (same_phase && vec_ok[k] && phase != 0) {
+            const int64_t h0 = (int64_t)((kTileAlignBytes - phase) / sizeof(float));
+            if (h0 < numel[k])
+                head[k] = h0;
+        }
+    }
+
+    plan.ptr_bytes = ptr_table_bytes(num_tensors, W);
+    const size_t chunk_bytes = align_up((size_t)std::max<int64_t>(max_chunks, 1) * 16, 256);
+    plan.image.assign(plan.ptr_bytes + chunk_bytes, 0);
+    uint64_t *pt = reinterpret_cast<uint64_t *>(plan.image.data());
+    for (int k = 0; k < num_tensors; ++k) {
+        uint64_t *row = pt + (size_t)k * stride;
+        row[0] = (uint64_t)(uintptr_t)w[k];
+        row[1] = (uint64_t)(uintptr_t)mom[k];
+        for (int m = 0; m < W; ++m) {
+            row[2 + m] = (uint64_t)(uintptr_t)grads[m][k];
+            row[2 + W + m] = (uint64_t)(uintptr_t)local_w[m][k];
+        }
+    }
+    // chunk table: full chunks of all tensors first, ragged ones (heads and
+    // tails) after them, so the short pieces fill the end of the launch
+    uint32_t *ct = reinterpret_cast<uint32_t *>(plan.image.data() + plan.ptr_bytes);
+    int64_t c = 0;
+    const int64_t C = plan.tuning.chunk_elems;
+    auto emit = [&](int k, int64_t off, int64_t cnt) {
+        uint32_t *dsc = ct + c * 4;
+        dsc[0] = (uint32_t)k | (vec_ok[k] ? kVecFlag : 0u);
+        dsc[1] = (uint32_t)cnt;
+        dsc[2] = (uint32_t)((uint64_t)off & 0xffffffffu);
+        dsc[3] = (uint32_t)((uint64_t)off >> 32);
+        ++c;
+    };
+    for (int pass = 0; pass < 2; ++pass) {
+        for (int k = 0; k < num_tensors; ++k) {
+            const int64_t n = numel[k];
+            const int64_t body = n - head[k];
+            const int64_t nfull = body / C;
+            if (pass == 0) {
+                for (int64_t j = 0; j < nfull; ++j)
+                    emit(k, head[k] + j * C, C);
+            } else {
+                if (head[k] > 0)
+                    emit(k, 0, head[k]);
+                if (body > nfull * C)
+                    emit(k, head[k] + nfull * C, body - nfull * C);
+            }
+        }
+    }
+    plan.nchunks = c;
+    return ODSGD_OK;
+}
+
 using KernelFn = void (*)(KernelArgs);
 
 template <int MODE, int RULE>
@@ -601,7 +714,6 @@ struct odsgd_handle {
     std::vector<int64_t> numel;
     std::vector<Range> ranges;           // every registered buffer, for alias checks of later registrations
     size_t base_ranges;                  // how many of them odsgd_init registered
-    std::vector<unsigned char> staging;  // host image of the tables (kept alive for the upload)
 };
 
 namespace {
@@ -709,68 +821,19 @@ int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel, float 
     if (!out)
         return ODSGD_EINVAL;
     *out = nullptr;
-    if (num_tensors < 1 || !numel || !w || !mom || !grads || !local_w || num_workers < 1 ||
-        num_workers > ODSGD_MAX_WORKERS || !workspace)
+    if (!workspace)
         return ODSGD_EINVAL;
-    for (int m = 0; m < num_workers; ++m)
-        if (!grads[m] || !local_w[m])
-            return ODSGD_EINVAL;
-
-    const Tuning tuning = current_tuning();
-    int err = 0;
-    const int64_t max_chunks = count_chunks(num_tensors, numel, tuning.chunk_elems, &err);
-    if (max_chunks < 0)
-        return err;
-
-    const int W = num_workers;
-    const int stride = 2 + 3 * W;
-    const int registered = 2 + 2 * W;  // the MeanSquare columns stay null until a rule registers them
-
-    // pointer checks: non-null and 4-byte aligned where the tensor is not empty
-    std::vector<Range> ranges;
-    ranges.reserve((size_t)num_tensors * stride);
-    std::vector<unsigned char> vec_ok(num_tensors, 1);
-    // elements before the first tile boundary, when every array of the tensor sits
-    // at the same offset from one (packed buckets); 0 = chunks start at element 0
-    std::vector<int64_t> head(num_tensors, 0);
-    for (int k = 0; k < num_tensors; ++k) {
-        if (numel[k] == 0)
-            continue;
-        const size_t bytes = (size_t)numel[k] * sizeof(float);
-        const uintptr_t phase = (uintptr_t)w[k] % kTileAlignBytes;
-        bool same_phase = true;
-        for (int j = 0; j < registered; ++j) {
-            const void *p = j == 0   ? (const void *)w[k]
-                            : j == 1 ? (const void *)mom[k]
-                            : j < 2 + W ? (const void *)grads[j - 2][k]
-                                        : (const void *)local_w[j - 2 - W][k];
-            if (!p)
-                return ODSGD_EINVAL;
-            const uintptr_t a = (uintptr_t)p;
-            if (a % 4 != 0)
-                return ODSGD_EALIGN;
-            if (a % 16 != 0)
-                vec_ok[k] = 0;
-            if (a % kTileAlignBytes != phase)
-                same_phase = false;
-            const bool is_output = (j < 2) || (j >= 2 + W);
-            ranges.push_back(Range{a, a + bytes, is_output});
-        }
-        if (same_phase && vec_ok[k] && phase != 0) {
-            const int64_t h0 = (int64_t)((kTileAlignBytes - phase) / sizeof(float));
-            if (h0 < numel[k])
-                head[k] = h0;
-        }
-    }
+    Plan plan;
+    int rc = make_plan(plan, num_tensors, numel, w, mom, grads, local_w, num_workers);
+    if (rc != ODSGD_OK)
+        return rc;
     if ((uintptr_t)workspace % 256 != 0)
         return ODSGD_EALIGN;
-    const size_t ptr_bytes = ptr_table_bytes(num_tensors, W);
-    const size_t chunk_bytes = align_up((size_t)std::max<int64_t>(max_chunks, 1) * 16, 256);
-    if (workspace_bytes < ptr_bytes + chunk_bytes)
+    if (workspace_bytes < plan.image.size())
         return ODSGD_ENOSPC;
-    ranges.push_back(Range{(uintptr_t)workspace, (uintptr_t)workspace + ptr_bytes + chunk_bytes, true});
+    plan.ranges.push_back(Range{(uintptr_t)workspace, (uintptr_t)workspace + plan.image.size(), true});
     {
-        std::vector<Range> sorted = ranges;
+        std::vector<Range> sorted = plan.ranges;
         if (ranges_alias(sorted))
             return ODSGD_EALIAS;
     }
@@ -779,17 +842,17 @@ int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel, float 
     if (!h)
         return ODSGD_EINVAL;
     h->num_tensors = num_tensors;
-    h->num_workers = W;
-    h->nchunks = 0;  // set once the chunk table is built
-    h->tuning = tuning;
+    h->num_workers = num_workers;
+    h->nchunks = plan.nchunks;
+    h->tuning = plan.tuning;
     h->iteration = 0;
     h->warmup_steps = 0;
     h->rule = odsgd_local_rule{ODSGD_LOCAL_SGD, 0.0f, 0.0f, 0.0f, 0.0f};
     h->numel.assign(numel, numel + num_tensors);
-    h->ranges = std::move(ranges);
+    h->ranges = std::move(plan.ranges);
     h->base_ranges = h->ranges.size();
     h->d_ptrs = workspace;
-    h->d_chunks = (const unsigned char *)workspace + ptr_bytes;
+    h->d_chunks = (const unsigned char *)workspace + plan.ptr_bytes;
 
     hipError_t e = hipGetDevice(&h->device);
     if (e == hipSuccess) {
@@ -802,66 +865,40 @@ int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel, float 
         e = hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, h->device);
         h->lds_per_cu = lds > 0 ? lds : 160 * 1024;
     }
-    if (e != hipSuccess) {
-        g_last_hip_error = e;
-        delete h;
-        return ODSGD_EHIP;
-    }
-
-    // host image of both tables
-    h->staging.assign(ptr_bytes + chunk_bytes, 0);
-    uint64_t *pt = reinterpret_cast<uint64_t *>(h->staging.data());
-    for (int k = 0; k < num_tensors; ++k) {
-        uint64_t *row = pt + (size_t)k * stride;
-        row[0] = (uint64_t)(uintptr_t)w[k];
-        row[1] = (uint64_t)(uintptr_t)mom[k];
-        for (int m = 0; m < W; ++m) {
-            row[2 + m] = (uint64_t)(uintptr_t)grads[m][k];
-            row[2 + W + m] = (uint64_t)(uintptr_t)local_w[m][k];
-        }
-    }
-    // chunk table: full chunks of all tensors first, ragged ones (heads and
-    // tails) after them, so the short pieces fill the end of the launch
-    uint32_t *ct = reinterpret_cast<uint32_t *>(h->staging.data() + ptr_bytes);
-    int64_t c = 0;
-    const int64_t C = tuning.chunk_elems;
-    auto emit = [&](int k, int64_t off, int64_t cnt) {
-        uint32_t *dsc = ct + c * 4;
-        dsc[0] = (uint32_t)k | (vec_ok[k] ? kVecFlag : 0u);
-        dsc[1] = (uint32_t)cnt;
-        dsc[2] = (uint32_t)((uint64_t)off & 0xffffffffu);
-        dsc[3] = (uint32_t)((uint64_t)off >> 32);
-        ++c;
-    };
-    for (int pass = 0; pass < 2; ++pass) {
-        for (int k = 0; k < num_tensors; ++k) {
-            const int64_t n = numel[k];
-            const int64_t body = n - head[k];
-            const int64_t nfull = body / C;
-            if (pass == 0) {
-                for (int64_t j = 0; j < nfull; ++j)
-                    emit(k, head[k] + j * C, C);
-            } else {
-                if (head[k] > 0)
-                    emit(k, 0, head[k]);
-                if (body > nfull * C)
-                    emit(k, head[k] + nfull * C, body - nfull * C);
-            }
-        }
-    }
-    h->nchunks = c;
-
-    e = hipMemcpyAsync(workspace, h->staging.data(), h->staging.size(), hipMemcpyHostToDevice,
-                       (hipStream_t)stream);
     if (e == hipSuccess)
-        e = hipStreamSynchronize((hipStream_t)stream);
+        e = hipMemcpyAsync(workspace, plan.image.data(), plan.image.size(), hipMemcpyHostToDevice,
+                           (hipStream_t)stream);
+    if (e == hipSuccess)
+        e = hipStreamSynchronize((hipStream_t)stream);  // plan.image must outlive the copy
     if (e != hipSuccess) {
         g_last_hip_error = e;
         delete h;
         return ODSGD_EHIP;
     }
-    std::vector<unsigned char>().swap(h->staging);
     *out = h;
+    return ODSGD_OK;
+}
+
+int odsgd_plan_host(int num_tensors, const int64_t *numel, float *const *w, float *const *mom,
+                    const float *const *const *grads, float *const *const *local_w, int num_workers,
+                    void *image, size_t image_bytes, int64_t *num_chunks, size_t *chunk_table_offset)
+{
+    if (!image || !num_chunks || !chunk_table_offset)
+        return ODSGD_EINVAL;
+    Plan plan;
+    int rc = make_plan(plan, num_tensors, numel, w, mom, grads, local_w, num_workers);
+    if (rc != ODSGD_OK)
+        return rc;
+    {
+        std::vector<Range> sorted = plan.ranges;
+        if (ranges_alias(sorted))
+            return ODSGD_EALIAS;
+    }
+    if (image_bytes < plan.image.size())
+        return ODSGD_ENOSPC;
+    std::memcpy(image, plan.image.data(), plan.image.size());
+    *num_chunks = plan.nchunks;
+    *chunk_table_offset = plan.ptr_bytes;
     return ODSGD_OK;
 }
 
