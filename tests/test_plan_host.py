@@ -118,3 +118,28 @@ def test_plan_rejects_what_init_rejects():
     with pytest.raises(B.OdsgdError) as e:
         B.odsgd_plan_host([100], [w[0] + 2], v, g, u, 1)
     assert e.value.code == B.ODSGD_EALIGN
+
+
+def test_host_code_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """Compile the library's host code with ASan + UBSan (device code untouched) together
+    with a driver that builds plans for hundreds of random shapes / alignments / error
+    cases; it must finish clean."""
+    import shutil
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if not (os.path.exists(hipcc) or shutil.which(hipcc)):
+        pytest.skip("hipcc not available")
+    exe = str(tmp_path / "plan_sanitized")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-ffp-contract=off",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined",
+           "-I", os.path.join(root, "include"),
+           os.path.join(root, "paper_2005_06728_amd", "csrc", "odsgd.hip"),
+           "-x", "c++", os.path.join(root, "tests", "plan_sanitizer_driver.cpp"), "-o", exe]
+    subprocess.run(cmd, check=True, capture_output=True)
+    env = dict(os.environ, ASAN_OPTIONS="verify_asan_link_order=0:detect_leaks=1")
+    r = subprocess.run([exe], env=env, capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert r.stdout.startswith("ok plans=")
