@@ -175,7 +175,7 @@ def test_probe_copy():
 # ---------------------------------------------------------------------------
 # worker counts (templated and generic kernels), ragged sizes, guard bands
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("W", [1, 2, 3, 4, 5, 7, 8, 12, 16, 17])
+@pytest.mark.parametrize("W", [1, 2, 3, 4, 5, 7, 8, 12, 16, 17, 64])
 def test_worker_counts_ragged_sizes_all_entry_points(W):
     say("W=%d sizes=%s" % (W, RAGGED))
     st, arenas, gen = custom_state(RAGGED, W, seed=100 + W)
@@ -474,4 +474,22 @@ def test_tensor_beyond_32_bit_element_offsets():
     # every element was written exactly once: no canary left in the local weights
     for lo in range(0, n, step):
         assert not bool(torch.any(u[lo:min(n, lo + step)] == CANARY))
+    eng.close()
+
+
+def test_thousands_of_tiny_tensors():
+    """K = 3000 tensors of 1..300 elements: one ragged chunk (or two) each, a 3000-row pointer table."""
+    rng = np.random.default_rng(5)
+    sizes = [int(x) for x in rng.integers(1, 300, 3000)]
+    W = 2
+    st, arenas, gen = custom_state(sizes, W, seed=41)
+    hs = host_state(st)
+    eng = make_engine(st)
+    hy = (0.05, 0.02, 0.9, 1e-3, 0.0)
+    oh = oracle_hyper(hy)
+    for _ in range(2):
+        eng.step(hy)
+        oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], **oh)
+    assert compare(st, hs)[0] == 0
+    assert arenas_intact(arenas)
     eng.close()
