@@ -493,3 +493,25 @@ def test_thousands_of_tiny_tensors():
     assert compare(st, hs)[0] == 0
     assert arenas_intact(arenas)
     eng.close()
+
+
+def test_two_handles_on_two_streams_are_independent():
+    states, engines, hosts, streams = [], [], [], []
+    for seed, sizes, W in ((51, [30000, 77, 4096], 4), (52, [12345, 1000], 8)):
+        st, _, _ = custom_state(sizes, W, seed=seed)
+        states.append(st)
+        hosts.append(host_state(st))
+        engines.append(make_engine(st))
+        streams.append(torch.cuda.Stream())
+    torch.cuda.synchronize()
+    hy = (0.05, 0.02, 0.9, 1e-3, 0.0)
+    for _ in range(5):
+        for eng, s in zip(engines, streams):
+            eng.step(hy, stream=s)
+    for s in streams:
+        s.synchronize()
+    for st, hs, eng in zip(states, hosts, engines):
+        for _ in range(5):
+            oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], **oracle_hyper(hy))
+        assert compare(st, hs)[0] == 0
+        eng.close()
