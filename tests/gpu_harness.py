@@ -8,7 +8,13 @@ from helpers import max_rel_err, same_bits
 from oracle import odsgd_oracle as oracle
 from paper_2005_06728_amd import binding as B
 
+DEV = "cuda:0"
+CANARY = 1234.5
 TOL = 1e-6  # max relative error bar for fp32 (the arithmetic is order-fixed, so bitwise equality is expected)
+
+
+def say(msg):
+    print(msg, flush=True)
 
 
 def to_host(lst):
@@ -68,3 +74,58 @@ def oracle_hyper(h):
     """The C ABI takes floats; hand the oracle the same binary32 values."""
     return dict(lr=f32(h[0]), local_lr=f32(h[1]), momentum=f32(h[2]),
                 weight_decay=f32(h[3]), grad_scale=f32(h[4]))
+
+
+# ---------------------------------------------------------------------------
+# custom tensor lists inside guarded arenas
+# ---------------------------------------------------------------------------
+class Arena:
+    """One flat buffer per role; tensors are views separated by canary gaps."""
+
+    def __init__(self, sizes, shift=0, gap=64):
+        offs, o = [], gap + shift
+        for n in sizes:
+            offs.append(o)
+            o += ((n + 3) // 4) * 4 + gap  # next view starts 16-byte aligned (+ shift elements)
+        self.buf = torch.full((o + gap,), CANARY, dtype=torch.float32, device=DEV)
+        self.views = [self.buf[a:a + n] for a, n in zip(offs, sizes)]
+        self.mask = torch.ones(o + gap, dtype=torch.bool, device=DEV)
+        for a, n in zip(offs, sizes):
+            self.mask[a:a + n] = False
+
+    def intact(self):
+        return bool(torch.all(self.buf[self.mask] == CANARY))
+
+
+def custom_state(sizes, W, seed, shifts=None, wstd=0.05, gstd=1e-3):
+    """shifts: per-role element shift (0 = 16-byte aligned views, 1..3 = only 4-byte aligned)."""
+    shifts = shifts or {}
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed)
+    arenas = {"w": Arena(sizes, shifts.get("w", 0)), "v": Arena(sizes, shifts.get("v", 0)),
+              "g": [Arena(sizes, shifts.get("g", 0)) for _ in range(W)],
+              "u": [Arena(sizes, shifts.get("u", 0)) for _ in range(W)]}
+    st = {"w": arenas["w"].views, "v": arenas["v"].views,
+          "g": [a.views for a in arenas["g"]], "u": [a.views for a in arenas["u"]]}
+    for t in st["w"]:
+        t.normal_(0, wstd, generator=gen)
+    for t in st["v"]:
+        t.normal_(0, 1e-3, generator=gen)
+    for m in range(W):
+        for t in st["g"][m]:
+            t.normal_(0, gstd, generator=gen)
+    return st, arenas, gen
+
+
+def arenas_intact(arenas):
+    return (arenas["w"].intact() and arenas["v"].intact()
+            and all(a.intact() for a in arenas["g"]) and all(a.intact() for a in arenas["u"]))
+
+
+def regen_grads(st, gen, gstd=1e-3):
+    for r in st["g"]:
+        for t in r:
+            t.normal_(0, gstd, generator=gen)
+
+
+RAGGED = [0, 1, 3, 4, 5, 255, 256, 257, 1023, 1024, 1025, 4096, 4097, 8191, 3 * 4096 + 7, 20000]

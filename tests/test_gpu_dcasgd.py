@@ -9,7 +9,7 @@ from helpers import same_bits
 from oracle import odsgd_oracle as oracle
 from paper_2005_06728_amd import binding as B
 from paper_2005_06728_amd import workloads as wl
-from test_gpu_parity import RAGGED, arenas_intact, custom_state, regen_grads, say, Arena
+from gpu_harness import RAGGED, Arena, arenas_intact, custom_state, regen_grads, say
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
