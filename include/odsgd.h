@@ -57,6 +57,7 @@ extern "C" {
 #define ODSGD_ENOSPC (-4) /* workspace smaller than odsgd_workspace_bytes() */
 #define ODSGD_EHIP (-5)   /* a HIP runtime call failed */
 #define ODSGD_ERANGE (-6) /* sizes exceed what the tables can index (a tensor >= 2^40 elements, > 2^31-2 chunks) */
+#define ODSGD_ESTALE (-7) /* handle of odsgd_init_static whose table memory a later odsgd_init_static took over */
 
 #define ODSGD_MAX_WORKERS 64
 
@@ -114,6 +115,38 @@ int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel,
                const float *const *const *grads, float *const *const *local_w,
                int num_workers, void *workspace, size_t workspace_bytes,
                void *stream);
+
+/*
+ * odsgd_init for callers that cannot allocate device memory (code that runs
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): the same registration, but the chunk and pointer tables go into
+ * a fixed array of ODSGD_STATIC_PLAN_BYTES that is part of the library's code
+ * object (one copy per GPU, held until the process ends) instead of a caller
+ * workspace.  The call allocates no device memory and neither does anything
+ * done with the handle; host heap is used for the handle only.  Every other
+ * argument, every check and every later call (odsgd_step, odsgd_local_update,
+ * odsgd_global_update, odsgd_ssgd_step, odsgd_set_local_rule, ...) is as for
+ * odsgd_init, and results are bitwise the same.
+ *
+ * Limit: odsgd_workspace_bytes(num_tensors, numel, num_workers) must not exceed
+ * ODSGD_STATIC_PLAN_BYTES (16 MiB: 16 bytes per 256 elements plus
+ * 8*(2 + 3*num_workers) bytes per tensor, i.e. about 2.6e8 parameters);
+ * ODSGD_ENOSPC otherwise, before any device is touched.
+ *
+ * All static registrations on one GPU share that GPU's array.  A new call
+ * overwrites it, so (a) handles of earlier odsgd_init_static calls on the same
+ * GPU become stale: their launches return ODSGD_ESTALE and enqueue nothing;
+ * (b) the caller must make sure no kernel of such an earlier handle is still
+ * running or enqueued when the new call is made -- the upload would race with
+ * it.  The array keeps the previous registration's bytes; each call uploads its
+ * complete table image (padding and unset columns included), so no launch reads
+ * anything left over.  Handles of odsgd_init are unaffected.
+ */
+#define ODSGD_STATIC_PLAN_BYTES (16u << 20)
+int odsgd_init_static(odsgd_handle **out, int num_tensors, const int64_t *numel,
+                      float *const *w, float *const *mom,
+                      const float *const *const *grads, float *const *const *local_w,
+                      int num_workers, void *stream);
 
 /*
  * Inspection aid: build, in host memory and without touching any device, the

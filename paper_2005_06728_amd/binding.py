@@ -19,6 +19,8 @@ ODSGD_EALIAS = -3
 ODSGD_ENOSPC = -4
 ODSGD_EHIP = -5
 ODSGD_ERANGE = -6
+ODSGD_ESTALE = -7
+ODSGD_STATIC_PLAN_BYTES = 16 << 20
 ODSGD_MAX_WORKERS = 64
 ODSGD_LOCAL_SGD = 0
 ODSGD_LOCAL_DCASGD_C = 1
@@ -66,6 +68,8 @@ def lib():
     L.odsgd_init.restype = ctypes.c_int
     L.odsgd_init.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64p, vp, vp, vp, vp,
                              ctypes.c_int, vp, ctypes.c_size_t, vp]
+    L.odsgd_init_static.restype = ctypes.c_int
+    L.odsgd_init_static.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64p, vp, vp, vp, vp, ctypes.c_int, vp]
     L.odsgd_plan_host.restype = ctypes.c_int
     L.odsgd_plan_host.argtypes = [ctypes.c_int, i64p, vp, vp, vp, vp, ctypes.c_int, vp, ctypes.c_size_t,
                                   ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_size_t)]
@@ -131,6 +135,22 @@ def odsgd_init(numel, w_ptrs, mom_ptrs, grad_ptrs, local_ptrs, num_workers,
     del g_keep, u_keep, w_row, m_row, n_arr
     if rc != ODSGD_OK:
         raise OdsgdError(rc, "odsgd_init")
+    return out.value
+
+
+def odsgd_init_static(numel, w_ptrs, mom_ptrs, grad_ptrs, local_ptrs, num_workers, stream=0):
+    """odsgd_init without a workspace: the tables go into the library's static device array."""
+    out = ctypes.c_void_p()
+    g_top, g_keep = _ptr_rows(grad_ptrs)
+    u_top, u_keep = _ptr_rows(local_ptrs)
+    w_row, m_row, n_arr = _ptr_row(w_ptrs), _ptr_row(mom_ptrs), _i64_array(numel)
+    rc = lib().odsgd_init_static(ctypes.byref(out), len(numel), n_arr,
+                                 ctypes.cast(w_row, ctypes.c_void_p), ctypes.cast(m_row, ctypes.c_void_p),
+                                 ctypes.cast(g_top, ctypes.c_void_p), ctypes.cast(u_top, ctypes.c_void_p),
+                                 int(num_workers), ctypes.c_void_p(int(stream)))
+    del g_keep, u_keep, w_row, m_row, n_arr
+    if rc != ODSGD_OK:
+        raise OdsgdError(rc, "odsgd_init_static")
     return out.value
 
 
@@ -241,22 +261,26 @@ class Engine:
     """Convenience owner of a handle: keeps the registered tensors and the
     workspace alive and forwards to the C entry points of the same name."""
 
-    def __init__(self, w, mom, grads, local_w, warmup_steps=0, stream=None):
+    def __init__(self, w, mom, grads, local_w, warmup_steps=0, stream=None, static_plan=False):
+        """static_plan=True registers through odsgd_init_static (no workspace tensor)."""
         self.w, self.mom, self.grads, self.local_w = w, mom, grads, local_w
         W = len(grads)
         for t in list(w) + list(mom) + [x for r in grads for x in r] + [x for r in local_w for x in r]:
             if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
                 raise ValueError("tensors must be contiguous fp32 CUDA tensors")
         numel = [t.numel() for t in w]
-        nbytes = odsgd_workspace_bytes(numel, W)
-        if nbytes == 0:
-            raise OdsgdError(ODSGD_EINVAL, "odsgd_workspace_bytes")
-        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=w[0].device)
-        self.handle = odsgd_init(
-            numel, [t.data_ptr() for t in w], [t.data_ptr() for t in mom],
-            [[t.data_ptr() for t in r] for r in grads],
-            [[t.data_ptr() for t in r] for r in local_w],
-            W, self.workspace.data_ptr(), nbytes, _stream(stream))
+        ptrs = ([t.data_ptr() for t in w], [t.data_ptr() for t in mom],
+                [[t.data_ptr() for t in r] for r in grads], [[t.data_ptr() for t in r] for r in local_w])
+        self.handle = None
+        if static_plan:
+            self.workspace = None
+            self.handle = odsgd_init_static(numel, *ptrs, W, _stream(stream))
+        else:
+            nbytes = odsgd_workspace_bytes(numel, W)
+            if nbytes == 0:
+                raise OdsgdError(ODSGD_EINVAL, "odsgd_workspace_bytes")
+            self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=w[0].device)
+            self.handle = odsgd_init(numel, *ptrs, W, self.workspace.data_ptr(), nbytes, _stream(stream))
         if warmup_steps:
             odsgd_set_warmup(self.handle, warmup_steps)
 

@@ -30,12 +30,19 @@
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
 #include "odsgd.h"
 
 #pragma clang fp contract(off)
+
+// Table storage of odsgd_init_static: one array per GPU, part of the loaded code
+// object, alive until the process ends.  In host code this name is only a
+// handle for hipGetSymbolAddress; the device address it yields (one per device)
+// is what kernels and copies are given.
+static __device__ __align__(256) unsigned char odsgd_static_plan[ODSGD_STATIC_PLAN_BYTES];
 
 namespace {
 
@@ -714,6 +721,8 @@ struct odsgd_handle {
     std::vector<int64_t> numel;
     std::vector<Range> ranges;           // every registered buffer, for alias checks of later registrations
     size_t base_ranges;                  // how many of them odsgd_init registered
+    bool static_plan;                    // tables live in the per-device static array
+    uint64_t static_generation;          // which registration of that array this handle is
 };
 
 namespace {
@@ -760,8 +769,44 @@ size_t occupancy_cap_lds_bytes(const odsgd_handle *h, int mode, int wcount)
     return bytes;
 }
 
+// Per-device address of odsgd_static_plan and the number of registrations it has
+// seen; only the latest registration's handle may still launch.
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+void *g_static_ptr[kMaxDevices] = {};
+uint64_t g_static_generation[kMaxDevices] = {};
+
+// Device address of the static array on `device`, which must be the current device.
+int static_plan_address(int device, void **out)
+{
+    if (device < 0 || device >= kMaxDevices)
+        return ODSGD_EINVAL;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[device]) {
+        void *p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(odsgd_static_plan));
+        if (e != hipSuccess || !p) {
+            g_last_hip_error = (e != hipSuccess) ? e : hipErrorInvalidSymbol;
+            return ODSGD_EHIP;
+        }
+        g_static_ptr[device] = p;
+    }
+    *out = g_static_ptr[device];
+    return ODSGD_OK;
+}
+
+bool handle_is_stale(const odsgd_handle *h)
+{
+    if (!h->static_plan)
+        return false;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    return g_static_generation[h->device] != h->static_generation;
+}
+
 int launch(odsgd_handle *h, int mode, int wfirst, int wcount, const odsgd_hyper *hy, void *stream)
 {
+    if (handle_is_stale(h))
+        return ODSGD_ESTALE;
     if (h->nchunks == 0)
         return ODSGD_OK;
     KernelArgs a;
@@ -798,6 +843,96 @@ int launch(odsgd_handle *h, int mode, int wfirst, int wcount, const odsgd_hyper 
     return ODSGD_OK;
 }
 
+// Shared by odsgd_init (tables in the caller's workspace) and odsgd_init_static
+// (tables in the per-device static array; `workspace` is then looked up here,
+// after every check that needs no device has passed).
+int init_common(odsgd_handle **out, int num_tensors, const int64_t *numel, float *const *w, float *const *mom,
+                const float *const *const *grads, float *const *const *local_w, int num_workers,
+                void *workspace, size_t workspace_bytes, bool static_plan, void *stream)
+{
+    Plan plan;
+    int rc = make_plan(plan, num_tensors, numel, w, mom, grads, local_w, num_workers);
+    if (rc != ODSGD_OK)
+        return rc;
+    if (!static_plan && (uintptr_t)workspace % 256 != 0)
+        return ODSGD_EALIGN;
+    if (workspace_bytes < plan.image.size())
+        return ODSGD_ENOSPC;
+
+    int device = 0;
+    if (static_plan) {
+        // the caller's buffers cannot overlap the library's own array, but they may
+        // not overlap each other either
+        std::vector<Range> sorted = plan.ranges;
+        if (ranges_alias(sorted))
+            return ODSGD_EALIAS;
+        hipError_t e = hipGetDevice(&device);
+        if (e != hipSuccess) {
+            g_last_hip_error = e;
+            return ODSGD_EHIP;
+        }
+        rc = static_plan_address(device, &workspace);
+        if (rc != ODSGD_OK)
+            return rc;
+    }
+    plan.ranges.push_back(Range{(uintptr_t)workspace, (uintptr_t)workspace + plan.image.size(), true});
+    {
+        std::vector<Range> sorted = plan.ranges;
+        if (ranges_alias(sorted))
+            return ODSGD_EALIAS;
+    }
+
+    odsgd_handle *h = new (std::nothrow) odsgd_handle();
+    if (!h)
+        return ODSGD_EINVAL;
+    h->num_tensors = num_tensors;
+    h->num_workers = num_workers;
+    h->nchunks = plan.nchunks;
+    h->tuning = plan.tuning;
+    h->iteration = 0;
+    h->warmup_steps = 0;
+    h->rule = odsgd_local_rule{ODSGD_LOCAL_SGD, 0.0f, 0.0f, 0.0f, 0.0f};
+    h->numel.assign(numel, numel + num_tensors);
+    h->ranges = std::move(plan.ranges);
+    h->base_ranges = h->ranges.size();
+    h->d_ptrs = workspace;
+    h->d_chunks = (const unsigned char *)workspace + plan.ptr_bytes;
+    h->static_plan = static_plan;
+    h->static_generation = 0;
+
+    hipError_t e = hipGetDevice(&h->device);
+    if (e == hipSuccess) {
+        int cus = 0;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device);
+        h->num_cus = cus > 0 ? cus : 256;
+    }
+    if (e == hipSuccess) {
+        int lds = 0;
+        e = hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, h->device);
+        h->lds_per_cu = lds > 0 ? lds : 160 * 1024;
+    }
+    if (e == hipSuccess && static_plan) {
+        // from here on the array holds this registration: handles of earlier ones are stale
+        std::lock_guard<std::mutex> lock(g_static_mutex);
+        h->static_generation = ++g_static_generation[h->device];
+    }
+    // The whole image is uploaded, zero padding and the (still null) per-worker
+    // state columns included, so nothing a kernel reads is left over from an
+    // earlier registration of the same memory.
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(workspace, plan.image.data(), plan.image.size(), hipMemcpyHostToDevice,
+                           (hipStream_t)stream);
+    if (e == hipSuccess)
+        e = hipStreamSynchronize((hipStream_t)stream);  // plan.image must outlive the copy
+    if (e != hipSuccess) {
+        g_last_hip_error = e;
+        delete h;
+        return ODSGD_EHIP;
+    }
+    *out = h;
+    return ODSGD_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -823,60 +958,19 @@ int odsgd_init(odsgd_handle **out, int num_tensors, const int64_t *numel, float 
     *out = nullptr;
     if (!workspace)
         return ODSGD_EINVAL;
-    Plan plan;
-    int rc = make_plan(plan, num_tensors, numel, w, mom, grads, local_w, num_workers);
-    if (rc != ODSGD_OK)
-        return rc;
-    if ((uintptr_t)workspace % 256 != 0)
-        return ODSGD_EALIGN;
-    if (workspace_bytes < plan.image.size())
-        return ODSGD_ENOSPC;
-    plan.ranges.push_back(Range{(uintptr_t)workspace, (uintptr_t)workspace + plan.image.size(), true});
-    {
-        std::vector<Range> sorted = plan.ranges;
-        if (ranges_alias(sorted))
-            return ODSGD_EALIAS;
-    }
+    return init_common(out, num_tensors, numel, w, mom, grads, local_w, num_workers, workspace, workspace_bytes,
+                       false, stream);
+}
 
-    odsgd_handle *h = new (std::nothrow) odsgd_handle();
-    if (!h)
+int odsgd_init_static(odsgd_handle **out, int num_tensors, const int64_t *numel, float *const *w,
+                      float *const *mom, const float *const *const *grads, float *const *const *local_w,
+                      int num_workers, void *stream)
+{
+    if (!out)
         return ODSGD_EINVAL;
-    h->num_tensors = num_tensors;
-    h->num_workers = num_workers;
-    h->nchunks = plan.nchunks;
-    h->tuning = plan.tuning;
-    h->iteration = 0;
-    h->warmup_steps = 0;
-    h->rule = odsgd_local_rule{ODSGD_LOCAL_SGD, 0.0f, 0.0f, 0.0f, 0.0f};
-    h->numel.assign(numel, numel + num_tensors);
-    h->ranges = std::move(plan.ranges);
-    h->base_ranges = h->ranges.size();
-    h->d_ptrs = workspace;
-    h->d_chunks = (const unsigned char *)workspace + plan.ptr_bytes;
-
-    hipError_t e = hipGetDevice(&h->device);
-    if (e == hipSuccess) {
-        int cus = 0;
-        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device);
-        h->num_cus = cus > 0 ? cus : 256;
-    }
-    if (e == hipSuccess) {
-        int lds = 0;
-        e = hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, h->device);
-        h->lds_per_cu = lds > 0 ? lds : 160 * 1024;
-    }
-    if (e == hipSuccess)
-        e = hipMemcpyAsync(workspace, plan.image.data(), plan.image.size(), hipMemcpyHostToDevice,
-                           (hipStream_t)stream);
-    if (e == hipSuccess)
-        e = hipStreamSynchronize((hipStream_t)stream);  // plan.image must outlive the copy
-    if (e != hipSuccess) {
-        g_last_hip_error = e;
-        delete h;
-        return ODSGD_EHIP;
-    }
-    *out = h;
-    return ODSGD_OK;
+    *out = nullptr;
+    return init_common(out, num_tensors, numel, w, mom, grads, local_w, num_workers, nullptr,
+                       ODSGD_STATIC_PLAN_BYTES, true, stream);
 }
 
 int odsgd_plan_host(int num_tensors, const int64_t *numel, float *const *w, float *const *mom,
@@ -947,6 +1041,8 @@ int odsgd_set_local_rule(odsgd_handle *h, const odsgd_local_rule *rule, float *c
 {
     if (!h || !rule)
         return ODSGD_EINVAL;
+    if (handle_is_stale(h))
+        return ODSGD_ESTALE;
     if (rule->rule != ODSGD_LOCAL_SGD && rule->rule != ODSGD_LOCAL_DCASGD_C &&
         rule->rule != ODSGD_LOCAL_DCASGD_A && rule->rule != ODSGD_LOCAL_SGD_MOMENTUM)
         return ODSGD_EINVAL;
@@ -1052,6 +1148,7 @@ const char *odsgd_strerror(int code)
     case ODSGD_ENOSPC: return "workspace too small";
     case ODSGD_EHIP: return hipGetErrorString(g_last_hip_error);
     case ODSGD_ERANGE: return "tensor list too large for the chunk table";
+    case ODSGD_ESTALE: return "a later odsgd_init_static on this GPU took over the static table memory";
     default: return "unknown error code";
     }
 }

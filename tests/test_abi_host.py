@@ -90,6 +90,35 @@ def test_init_rejects_bad_arguments_without_a_device():
         assert e.value.code == B.ODSGD_EHIP
 
 
+def test_init_static_checks_arguments_and_size_before_any_device_work():
+    """The no-allocation registration shares odsgd_init's validation; what does not fit its
+    fixed table memory is refused with ODSGD_ENOSPC."""
+    good = dict(numel=[8], w_ptrs=[0x1000], mom_ptrs=[0x2000], grad_ptrs=[[0x3000]],
+                local_ptrs=[[0x4000]], num_workers=1)
+
+    def expect(code, **kw):
+        args = dict(good)
+        args.update(kw)
+        with pytest.raises(B.OdsgdError) as e:
+            B.odsgd_init_static(**args)
+        assert e.value.code == code, (e.value.code, kw)
+
+    expect(B.ODSGD_EINVAL, w_ptrs=[0])
+    expect(B.ODSGD_EINVAL, numel=[-3])
+    expect(B.ODSGD_EALIGN, mom_ptrs=[0x2002])
+    expect(B.ODSGD_EALIAS, local_ptrs=[[0x1010]])
+    expect(B.ODSGD_ERANGE, numel=[1 << 40])
+    # 2^28 elements -> 2^20 chunk descriptors of 16 bytes = exactly the 16 MiB, plus the pointer table
+    assert B.odsgd_workspace_bytes([1 << 28], 1) > B.ODSGD_STATIC_PLAN_BYTES
+    far = dict(w_ptrs=[1 << 40], mom_ptrs=[2 << 40], grad_ptrs=[[3 << 40]], local_ptrs=[[4 << 40]])
+    expect(B.ODSGD_ENOSPC, numel=[1 << 28], **far)
+    expect(B.ODSGD_ENOSPC, numel=[1 << 33], **far)
+    assert B.ODSGD_STATIC_PLAN_BYTES == 16 << 20
+    assert B.odsgd_strerror(B.ODSGD_ESTALE) not in ("", "success", "unknown error code")
+    if not torch.cuda.is_available():
+        expect(B.ODSGD_EHIP)   # valid arguments: fails only because there is no device here
+
+
 def test_calls_reject_null_handle():
     h = B.odsgd_hyper(0.1, 0.1, 0.9, 0.0, 0.0)
     L = B.lib()
