@@ -37,5 +37,46 @@ def build(force=True, defines=(), lib=LIB, extra=()):
     return lib
 
 
+def resource_usage(defines=()):
+    """Compile the device code once more with the compiler's kernel-resource-usage remarks
+    and return one row per kernel: (name, VGPRs, AGPRs, SGPRs, SGPR spills, VGPR spills,
+    scratch bytes per lane, occupancy in waves per SIMD).  Template arguments of
+    odsgd_kernel<W, MODE, RULE> are decoded from the mangled name."""
+    import re
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    cmd = [hipcc, *flags, *["-D" + d for d in defines], "--cuda-device-only", "-c", SRC, "-o", os.devnull,
+           "-Rpass-analysis=kernel-resource-usage"]
+    text = subprocess.run(cmd, check=True, capture_output=True, text=True).stderr
+    modes = {0: "od", 1: "ssgd", 2: "global", 3: "local", 4: "global_oop"}
+    rules = {0: "sgd", 1: "dcasgd_c", 2: "dcasgd_a", 3: "momentum"}
+    rows = []
+    for block in re.split(r"remark: Function Name: ", text)[1:]:
+        mangled = block.split()[0]
+
+        def field(key):
+            m = re.search(re.escape(key) + r": (\S+)", block)
+            return m.group(1) if m else "?"
+
+        m = re.search(r"odsgd_kernelILi(\d+)ELi(\d+)ELi(\d+)E", mangled)
+        if m:
+            wt, mode, rule = (int(x) for x in m.groups())
+            name = "odsgd_kernel<%s, %s, %s>" % (wt if wt else "any W", modes.get(mode, mode), rules.get(rule, rule))
+        else:
+            m = re.search(r"\d+(odsgd_[a-z_]+)", mangled)
+            name = m.group(1) if m else mangled
+        rows.append((name, field("VGPRs"), field("AGPRs"), field("TotalSGPRs"), field("SGPRs Spill"),
+                     field("VGPRs Spill"), field("ScratchSize [bytes/lane]"), field("Occupancy [waves/SIMD]")))
+    return cmd, rows
+
+
 if __name__ == "__main__":
-    print(build(force=True, defines=sys.argv[1:]))
+    if sys.argv[1:2] == ["--resource-usage"]:
+        cmd, rows = resource_usage(defines=sys.argv[2:])
+        print("command: " + " ".join(cmd))
+        print("| kernel | VGPRs | AGPRs | SGPRs | SGPR spills | VGPR spills | scratch B/lane | waves/SIMD |")
+        print("|---|---|---|---|---|---|---|---|")
+        for r in rows:
+            print("| " + " | ".join(r) + " |")
+    else:
+        print(build(force=True, defines=sys.argv[1:]))
