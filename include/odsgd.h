@@ -30,9 +30,15 @@
  *
  * Tuning.  Launch shape is chosen per call from the worker count and entry
  * point; three environment variables, read by odsgd_init, override it for
- * experiments and never change results: ODSGD_CHUNK_ELEMS (elements per chunk,
- * default 256), ODSGD_WAVES_PER_CU (resident wavefronts per compute unit; 0 =
- * automatic, negative = uncapped), ODSGD_BLOCKS_PER_CU (> 0: persistent grid).
+ * experiments and never change results: ODSGD_WAVES_PER_CU
+ * (resident wavefronts per compute unit; 0 = automatic, negative = uncapped),
+ * ODSGD_BLOCKS_PER_CU (> 0: persistent grid), ODSGD_PAIR_BIT (address bit that
+ * separates the two halves of a tile, default 15; 0 = contiguous tiles only).
+ *
+ * Layout advice.  The update runs fastest when, for each tensor, all arrays
+ * (w, mom, every grads[m] and local_w[m], state) start at the same offset from
+ * a 64 KiB boundary -- e.g. each role packed the same way into a bucket whose
+ * base is 64 KiB aligned, or every array 64 KiB aligned by itself.
  *
  * Execution model.  odsgd_local_update / odsgd_global_update / odsgd_step /
  * odsgd_ssgd_step enqueue one kernel on the given HIP stream and return
@@ -150,20 +156,60 @@ int odsgd_init_static(odsgd_handle **out, int num_tensors, const int64_t *numel,
 
 /*
  * Inspection aid: build, in host memory and without touching any device, the
- * exact table image odsgd_init would upload for these arguments -- the pointer
- * table (num_tensors rows of 2 + 3*num_workers 64-bit addresses:
- * w, mom, grads[0..], local_w[0..], then the per-worker state columns, zero
- * until a rule registers them) followed, at *chunk_table_offset, by
- * *num_chunks chunk descriptors of four 32-bit words {tensor index | bit 31 set
- * if the chunk takes 128-bit accesses, element count, element offset low,
- * element offset high}.  The pointers are only inspected, never dereferenced.
- * image must hold odsgd_workspace_bytes(...) bytes.  Same validation and error
- * codes as odsgd_init.
+ * exact table image odsgd_init would upload for these arguments.
+ *
+ * Pointer table: *num_rows rows of 4 + 3*num_workers 64-bit addresses
+ * [w, mom, grads[0..], local_w[0..], per-worker state[0..], w_alt, mom_alt]
+ * (the last W + 2 are zero until odsgd_set_local_rule / odsgd_set_double_buffer
+ * register them).  Rows follow the tensors in order; a tensor of more than 2^29
+ * elements takes one row per 2^29 elements (the addresses of row j are those of
+ * the tensor advanced by j * 2^29 elements), every other tensor one row.
+ *
+ * Chunk table, at *chunk_table_offset: *num_chunks descriptors of four 32-bit
+ * words {row index | bit 31 set if the chunk takes 128-bit accesses, element
+ * count, element offset inside the row, second-half word}.  With a second-half
+ * word of 0 the chunk is `count` consecutive elements.  Otherwise it is a
+ * two-half tile of 256 elements: 128 consecutive elements at the offset, and 128
+ * more starting 4*(32 + second-half word) elements after the offset (32 KiB
+ * later by default).  Such tiles are only used where all arrays of the tensor sit
+ * at the same offset from a 64 KiB boundary, and only inside aligned 64 KiB blocks.
+ *
+ * The pointers are only inspected, never dereferenced.  image must hold
+ * odsgd_workspace_bytes(...) bytes.  Same validation and error codes as odsgd_init.
  */
 int odsgd_plan_host(int num_tensors, const int64_t *numel, float *const *w, float *const *mom,
                     const float *const *const *grads, float *const *const *local_w,
-                    int num_workers, void *image, size_t image_bytes, int64_t *num_chunks,
-                    size_t *chunk_table_offset);
+                    int num_workers, void *image, size_t image_bytes, int64_t *num_rows,
+                    int64_t *num_chunks, size_t *chunk_table_offset);
+
+/*
+ * Inspection aid: the residency decision of a launch, for a CU described by the
+ * arguments instead of the one the process runs on.  Each entry point limits how
+ * many of its one-wavefront workgroups a CU holds at a time, because with many
+ * concurrent streams the memory system delivers more when fewer requests are in
+ * flight.  The limit is imposed by requesting dynamic LDS that the kernel never
+ * touches.  Side effect to know about: while such a kernel runs, that LDS is
+ * not available to kernels of other streams on the same CUs.
+ *   entry           ODSGD_ENTRY_*
+ *   rule            ODSGD_LOCAL_* in force (matters for STEP and LOCAL_UPDATE)
+ *   num_workers     workers the launch touches
+ *   waves_override  as ODSGD_WAVES_PER_CU: 0 = automatic, > 0 = that many, < 0 = no limit
+ *   lds_per_cu, lds_granule, max_request   LDS per CU, allocation granularity and
+ *                   largest request of one workgroup, in bytes
+ *   *waves_wanted   wavefronts per CU the launch aims at (0 = no limit)
+ *   *lds_bytes      the request that achieves it (0 = launched without a request:
+ *                   no limit wanted, or no request lands on the wanted count or,
+ *                   failing that, one below it)
+ *   *waves_achieved workgroups per CU under that request
+ * At run time the same search is driven by hipOccupancyMaxActiveBlocksPerMultiprocessor.
+ */
+#define ODSGD_ENTRY_STEP 0
+#define ODSGD_ENTRY_SSGD_STEP 1
+#define ODSGD_ENTRY_GLOBAL_UPDATE 2
+#define ODSGD_ENTRY_LOCAL_UPDATE 3
+int odsgd_plan_residency(int entry, int rule, int num_workers, int waves_override,
+                         size_t lds_per_cu, size_t lds_granule, size_t max_request,
+                         int *waves_wanted, size_t *lds_bytes, int *waves_achieved);
 
 /*
  * Local update (Alg. 2, training stage) with the local updater in force (default
@@ -176,10 +222,34 @@ int odsgd_local_update(odsgd_handle *h, int worker, const odsgd_hyper *hyper, vo
 
 /*
  * Global update (Alg. 1): W-way gradient reduce and momentum-SGD step on w and
- * mom, in place.  Uses lr, momentum, weight_decay, grad_scale.  Advances the
- * handle's iteration counter by one.
+ * mom, in place (out of place once odsgd_set_double_buffer has been called).
+ * Uses lr, momentum, weight_decay, grad_scale.  Advances the handle's iteration
+ * counter by one.
  */
 int odsgd_global_update(odsgd_handle *h, const odsgd_hyper *hyper, void *stream);
+
+/*
+ * Running the two halves of an iteration at the same time.  Section 3.1 notes
+ * that Push (which feeds the global update) and local_update only read the new
+ * gradient and can therefore run in parallel.  With an in-place global update
+ * that is not possible on one GPU, because the local update reads the very
+ * weights the global update overwrites.  This call registers a second pair of
+ * buffers (w_alt, mom_alt: host arrays [K] of device pointers, numel[k] floats
+ * each, caller-owned, contents irrelevant).  From then on odsgd_global_update
+ * reads the current pair and writes the other one, after which the roles swap;
+ * odsgd_local_update only reads the current pair.  Within one iteration the two
+ * calls may then be enqueued on two different streams with no ordering between
+ * them, and the results are bitwise those of odsgd_step.  Between iterations the
+ * caller orders the streams: iteration t+1 of either call must not start before
+ * iteration t of both has finished.  odsgd_step and odsgd_ssgd_step keep
+ * updating the current pair in place.  odsgd_current_buffers tells where the
+ * current weights and momentum are: 0 = the buffers given to odsgd_init, 1 = the
+ * second pair.  Must be called while the current pair is 0, and (the tables
+ * are rebuilt and uploaded on `stream`) while no kernel of this handle is
+ * running or enqueued on another stream.
+ */
+int odsgd_set_double_buffer(odsgd_handle *h, float *const *w_alt, float *const *mom_alt, void *stream);
+int odsgd_current_buffers(const odsgd_handle *h);
 
 /*
  * One iteration of the whole schedule of Alg. 2 in a single launch.  With i the
@@ -221,10 +291,12 @@ int odsgd_ssgd_step(odsgd_handle *h, const odsgd_hyper *hyper, void *stream);
  * must be initialised (to the weights the first gradients were taken at).
  * state: host array [W] of host arrays [K] of device pointers to the per-worker
  * state (MeanSquare for DCASGD_A, local velocity lv for SGD_MOMENTUM; numel[k]
- * floats each, 16-byte aligned, read and written, caller-owned, zero for a
- * fresh run); required for those two rules, ignored otherwise.  A new
- * registration replaces the previous one.  The pointers are uploaded on
- * `stream`; the call returns after the upload.  The paper gives lambda = 0.04
+ * floats each, 4-byte aligned (16 for the 128-bit path), read and written,
+ * caller-owned, zero for a fresh run); required for those two rules, ignored otherwise.  A new
+ * registration replaces the previous one.  The tables are rebuilt and uploaded
+ * on `stream` (how a tensor is tiled depends on the alignment of all its
+ * arrays, the state included); the call returns after the upload.  No kernel of
+ * this handle may be running or enqueued on another stream during the call.  The paper gives lambda = 0.04
  * (c), lambda = 2 with ms_decay 0.95 or 0 (a) and never states epsilon.
  */
 #define ODSGD_LOCAL_SGD 0
@@ -259,6 +331,16 @@ int odsgd_set_iteration(odsgd_handle *h, int64_t iteration);
  * yardstick for hardware byte counters and for the copy bandwidth of the box.
  */
 int odsgd_probe_copy(float *dst, const float *src, size_t numel, void *stream);
+
+/*
+ * Measurement aid, not part of the method: one launch with exactly the memory
+ * accesses of the fused odsgd_step with the SGD local updater on this handle
+ * (same tables, tiles, cache policies and residency) and none of its
+ * arithmetic: w and mom are read and written back unchanged, local_w[m]
+ * receives a copy of grads[m].  Its rate is the ceiling of this access shape on
+ * the machine at hand.  The iteration counter does not move.
+ */
+int odsgd_probe_streams(odsgd_handle *h, void *stream);
 
 /* Release the handle.  Does not touch device memory and does not synchronise:
  * the caller must not free the workspace while enqueued kernels may still run. */

@@ -72,7 +72,18 @@ def lib():
     L.odsgd_init_static.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64p, vp, vp, vp, vp, ctypes.c_int, vp]
     L.odsgd_plan_host.restype = ctypes.c_int
     L.odsgd_plan_host.argtypes = [ctypes.c_int, i64p, vp, vp, vp, vp, ctypes.c_int, vp, ctypes.c_size_t,
-                                  ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_size_t)]
+                                  ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64),
+                                  ctypes.POINTER(ctypes.c_size_t)]
+    L.odsgd_plan_residency.restype = ctypes.c_int
+    L.odsgd_plan_residency.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_size_t,
+                                       ctypes.c_size_t, ctypes.c_size_t, ctypes.POINTER(ctypes.c_int),
+                                       ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_int)]
+    L.odsgd_set_double_buffer.restype = ctypes.c_int
+    L.odsgd_set_double_buffer.argtypes = [vp, vp, vp, vp]
+    L.odsgd_current_buffers.restype = ctypes.c_int
+    L.odsgd_current_buffers.argtypes = [vp]
+    L.odsgd_probe_streams.restype = ctypes.c_int
+    L.odsgd_probe_streams.argtypes = [vp, vp]
     L.odsgd_local_update.restype = ctypes.c_int
     L.odsgd_local_update.argtypes = [vp, ctypes.c_int, hp, vp]
     for name in ("odsgd_global_update", "odsgd_step", "odsgd_ssgd_step"):
@@ -154,10 +165,13 @@ def odsgd_init_static(numel, w_ptrs, mom_ptrs, grad_ptrs, local_ptrs, num_worker
     return out.value
 
 
+ROW_ELEMS = 1 << 29  # elements per pointer-table row (see odsgd_plan_host in odsgd.h)
+
+
 def odsgd_plan_host(numel, w_ptrs, mom_ptrs, grad_ptrs, local_ptrs, num_workers):
     """Host-only: the tables odsgd_init would upload.  Returns (pointer_rows, chunks)
-    with pointer_rows[k] = list of 2 + 3W addresses and chunks = list of
-    (tensor, vec, count, offset)."""
+    with pointer_rows[r] = list of 4 + 3W addresses and chunks = list of
+    (row, vec, count, offset, second_half)."""
     import struct
     nbytes = odsgd_workspace_bytes(numel, num_workers)
     if nbytes == 0:
@@ -166,22 +180,45 @@ def odsgd_plan_host(numel, w_ptrs, mom_ptrs, grad_ptrs, local_ptrs, num_workers)
     g_top, g_keep = _ptr_rows(grad_ptrs)
     u_top, u_keep = _ptr_rows(local_ptrs)
     w_row, m_row, n_arr = _ptr_row(w_ptrs), _ptr_row(mom_ptrs), _i64_array(numel)
-    nch, off = ctypes.c_int64(), ctypes.c_size_t()
+    nrows, nch, off = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_size_t()
     rc = lib().odsgd_plan_host(len(numel), n_arr, ctypes.cast(w_row, ctypes.c_void_p),
                                ctypes.cast(m_row, ctypes.c_void_p), ctypes.cast(g_top, ctypes.c_void_p),
                                ctypes.cast(u_top, ctypes.c_void_p), int(num_workers), buf, nbytes,
-                               ctypes.byref(nch), ctypes.byref(off))
+                               ctypes.byref(nrows), ctypes.byref(nch), ctypes.byref(off))
     del g_keep, u_keep
     if rc != ODSGD_OK:
         raise OdsgdError(rc, "odsgd_plan_host")
-    stride = 2 + 3 * num_workers
+    stride = 4 + 3 * num_workers
     raw = buf.raw
-    rows = [list(struct.unpack_from("<%dQ" % stride, raw, k * stride * 8)) for k in range(len(numel))]
+    rows = [list(struct.unpack_from("<%dQ" % stride, raw, r * stride * 8)) for r in range(nrows.value)]
     chunks = []
     for c in range(nch.value):
-        t, cnt, lo, hi = struct.unpack_from("<4I", raw, off.value + 16 * c)
-        chunks.append((t & 0x7fffffff, bool(t >> 31), cnt, lo | (hi << 32)))
+        t, cnt, o, second = struct.unpack_from("<4I", raw, off.value + 16 * c)
+        chunks.append((t & 0x7fffffff, bool(t >> 31), cnt, o, second))
     return rows, chunks
+
+
+def chunk_elements(chunk):
+    """Element ranges (start, stop) inside its row that a chunk tuple of odsgd_plan_host covers."""
+    _, _, cnt, off, second = chunk
+    if second == 0:
+        return [(off, off + cnt)]
+    assert cnt == 256
+    return [(off, off + 128), (off + 4 * (32 + second), off + 4 * (32 + second) + 128)]
+
+
+ODSGD_ENTRY_STEP, ODSGD_ENTRY_SSGD_STEP, ODSGD_ENTRY_GLOBAL_UPDATE, ODSGD_ENTRY_LOCAL_UPDATE = 0, 1, 2, 3
+
+
+def odsgd_plan_residency(entry, rule, num_workers, waves_override=0, lds_per_cu=160 * 1024, lds_granule=1280,
+                         max_request=64 * 1024):
+    """Host-only: (waves wanted, LDS bytes requested, waves achieved) for a CU of the given LDS geometry."""
+    wanted, lds, got = ctypes.c_int(), ctypes.c_size_t(), ctypes.c_int()
+    _call("odsgd_plan_residency",
+          lib().odsgd_plan_residency(int(entry), int(rule), int(num_workers), int(waves_override), int(lds_per_cu),
+                                     int(lds_granule), int(max_request), ctypes.byref(wanted), ctypes.byref(lds),
+                                     ctypes.byref(got)))
+    return wanted.value, lds.value, got.value
 
 
 def _hyper(h):
@@ -232,6 +269,22 @@ def odsgd_set_local_rule(handle, rule, lam=0.0, ms_decay=0.0, epsilon=0.0, state
                                     _stream(stream))
     del keep
     _call("odsgd_set_local_rule", rc)
+
+
+def odsgd_set_double_buffer(handle, w_alt_ptrs, mom_alt_ptrs, stream=None):
+    """Register the second (w, mom) buffer pair: odsgd_global_update becomes out of place."""
+    a, b = _ptr_row(w_alt_ptrs), _ptr_row(mom_alt_ptrs)
+    _call("odsgd_set_double_buffer",
+          lib().odsgd_set_double_buffer(handle, ctypes.cast(a, ctypes.c_void_p), ctypes.cast(b, ctypes.c_void_p),
+                                        _stream(stream)))
+
+
+def odsgd_current_buffers(handle):
+    return int(lib().odsgd_current_buffers(handle))
+
+
+def odsgd_probe_streams(handle, stream=None):
+    _call("odsgd_probe_streams", lib().odsgd_probe_streams(handle, _stream(stream)))
 
 
 def odsgd_set_warmup(handle, warmup_steps):
@@ -292,6 +345,24 @@ class Engine:
         self.local_state = state
         ptrs = None if state is None else [[t.data_ptr() for t in r] for r in state]
         odsgd_set_local_rule(self.handle, rule, lam, ms_decay, epsilon, ptrs, stream, local_momentum)
+
+    def set_double_buffer(self, w_alt, mom_alt, stream=None):
+        """w_alt / mom_alt: [K] fp32 CUDA tensors, the second buffer pair of the out-of-place global update."""
+        self.w_alt, self.mom_alt = w_alt, mom_alt
+        odsgd_set_double_buffer(self.handle, [t.data_ptr() for t in w_alt], [t.data_ptr() for t in mom_alt], stream)
+
+    @property
+    def current_buffers(self):
+        return odsgd_current_buffers(self.handle)
+
+    def current_w(self):
+        return self.w_alt if self.current_buffers else self.w
+
+    def current_mom(self):
+        return self.mom_alt if self.current_buffers else self.mom
+
+    def probe_streams(self, stream=None):
+        odsgd_probe_streams(self.handle, stream)
 
     def step(self, hyper, stream=None):
         odsgd_step(self.handle, hyper, stream)

@@ -82,29 +82,37 @@ def oracle_hyper(h):
 class Arena:
     """One flat buffer per role; tensors are views separated by canary gaps."""
 
-    def __init__(self, sizes, shift=0, gap=64):
+    def __init__(self, sizes, shift=0, gap=64, block_phase=None):
+        """block_phase: if given, the arena's layout starts at an address that is block_phase
+        bytes past a 64 KiB boundary, so that arenas of equal layout put every tensor at the
+        same offset from such a boundary (the condition for two-half tiles)."""
         offs, o = [], gap + shift
         for n in sizes:
             offs.append(o)
             o += ((n + 3) // 4) * 4 + gap  # next view starts 16-byte aligned (+ shift elements)
-        self.buf = torch.full((o + gap,), CANARY, dtype=torch.float32, device=DEV)
-        self.views = [self.buf[a:a + n] for a, n in zip(offs, sizes)]
-        self.mask = torch.ones(o + gap, dtype=torch.bool, device=DEV)
+        total = o + gap + (16384 if block_phase is not None else 0)
+        self.buf = torch.full((total,), CANARY, dtype=torch.float32, device=DEV)
+        skip = 0
+        if block_phase is not None:
+            assert block_phase % 4 == 0 and self.buf.data_ptr() % 4 == 0
+            skip = ((block_phase - self.buf.data_ptr()) % 65536) // 4
+        self.views = [self.buf[skip + a:skip + a + n] for a, n in zip(offs, sizes)]
+        self.mask = torch.ones(total, dtype=torch.bool, device=DEV)
         for a, n in zip(offs, sizes):
-            self.mask[a:a + n] = False
+            self.mask[skip + a:skip + a + n] = False
 
     def intact(self):
         return bool(torch.all(self.buf[self.mask] == CANARY))
 
 
-def custom_state(sizes, W, seed, shifts=None, wstd=0.05, gstd=1e-3):
-    """shifts: per-role element shift (0 = 16-byte aligned views, 1..3 = only 4-byte aligned)."""
+def custom_state(sizes, W, seed, shifts=None, wstd=0.05, gstd=1e-3, block_phase=None):
+    """shifts: per-role element shift (0 = 16-byte aligned views, 1..3 = only 4-byte aligned).
+    block_phase: see Arena."""
     shifts = shifts or {}
     gen = torch.Generator(device=DEV)
     gen.manual_seed(seed)
-    arenas = {"w": Arena(sizes, shifts.get("w", 0)), "v": Arena(sizes, shifts.get("v", 0)),
-              "g": [Arena(sizes, shifts.get("g", 0)) for _ in range(W)],
-              "u": [Arena(sizes, shifts.get("u", 0)) for _ in range(W)]}
+    mk = lambda role: Arena(sizes, shifts.get(role, 0), block_phase=block_phase)
+    arenas = {"w": mk("w"), "v": mk("v"), "g": [mk("g") for _ in range(W)], "u": [mk("u") for _ in range(W)]}
     st = {"w": arenas["w"].views, "v": arenas["v"].views,
           "g": [a.views for a in arenas["g"]], "u": [a.views for a in arenas["u"]]}
     for t in st["w"]:

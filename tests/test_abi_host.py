@@ -153,3 +153,75 @@ def test_bench_refuses_more_than_one_gpu():
                        capture_output=True, text=True)
     assert r.returncode != 0
     assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+# ---------------------------------------------------------------------------
+# residency decision (dynamic-LDS request that limits workgroups per CU)
+# ---------------------------------------------------------------------------
+ENTRIES = {"step": B.ODSGD_ENTRY_STEP, "ssgd_step": B.ODSGD_ENTRY_SSGD_STEP,
+           "global_update": B.ODSGD_ENTRY_GLOBAL_UPDATE, "local_update": B.ODSGD_ENTRY_LOCAL_UPDATE}
+RULES = [B.ODSGD_LOCAL_SGD, B.ODSGD_LOCAL_DCASGD_C, B.ODSGD_LOCAL_DCASGD_A, B.ODSGD_LOCAL_SGD_MOMENTUM]
+
+
+def _model_occupancy(lds_per_cu, granule, request):
+    alloc = -(-request // granule) * granule
+    return lds_per_cu // alloc
+
+
+@pytest.mark.parametrize("lds_kib", [64, 128, 160])
+@pytest.mark.parametrize("granule", [256, 512, 1280])
+def test_residency_request_lands_on_the_wanted_wave_count(lds_kib, granule):
+    """For every entry point, local rule and worker count the dispatcher instantiates: the LDS
+    request yields the wanted number of resident wavefronts per CU (or one fewer where the
+    allocation granularity steps over it), whatever the CU's LDS size and granularity."""
+    lds = lds_kib * 1024
+    for name, entry in ENTRIES.items():
+        for rule in (RULES if name in ("step", "local_update") else RULES[:1]):
+            for W in (1, 2, 3, 4, 8, 12, 16, 17, 64):
+                wanted, req, got = B.odsgd_plan_residency(entry, rule, W, 0, lds, granule, 64 * 1024)
+                where = (name, rule, W, lds_kib, granule)
+                if wanted == 0:
+                    assert req == 0 and got == 0, where
+                    continue
+                assert 2 <= wanted <= 16, where
+                if req == 0:
+                    # refused: no request within the limit gets to wanted or wanted - 1
+                    assert all(not (max(2, wanted - 1) <= _model_occupancy(lds, granule, r) <= wanted)
+                               for r in range(256, 64 * 1024 + 1, 256)), where
+                    continue
+                assert req % 256 == 0 and req <= 64 * 1024, where
+                assert got == _model_occupancy(lds, granule, req), where
+                assert got in (wanted, wanted - 1) and got >= 2, where
+                if req > 256:   # the smallest such request: one step less would admit more wavefronts
+                    assert _model_occupancy(lds, granule, req - 256) > wanted, where
+
+
+def test_residency_choices_on_the_mi355x_geometry():
+    """160 KiB of LDS per CU: the wave counts the measured sweeps settled on."""
+    plan = lambda entry, rule, W, ov=0: B.odsgd_plan_residency(entry, rule, W, ov, 160 * 1024, 1280, 64 * 1024)
+    for entry, rule, W in ((B.ODSGD_ENTRY_STEP, B.ODSGD_LOCAL_SGD, 16), (B.ODSGD_ENTRY_STEP, B.ODSGD_LOCAL_SGD, 8),
+                           (B.ODSGD_ENTRY_STEP, B.ODSGD_LOCAL_DCASGD_A, 16),
+                           (B.ODSGD_ENTRY_LOCAL_UPDATE, B.ODSGD_LOCAL_SGD, 16),
+                           (B.ODSGD_ENTRY_GLOBAL_UPDATE, B.ODSGD_LOCAL_SGD, 16)):
+        wanted, req, got = plan(entry, rule, W)
+        assert got == wanted and req > 0, (entry, rule, W)
+    # few streams: no limit at all
+    assert plan(B.ODSGD_ENTRY_GLOBAL_UPDATE, B.ODSGD_LOCAL_SGD, 1) == (0, 0, 0)
+    # overrides: explicit count, and "no limit"
+    assert plan(B.ODSGD_ENTRY_STEP, B.ODSGD_LOCAL_SGD, 16, 7)[0::2] == (7, 7)
+    assert plan(B.ODSGD_ENTRY_STEP, B.ODSGD_LOCAL_SGD, 16, -1) == (0, 0, 0)
+    assert plan(B.ODSGD_ENTRY_STEP, B.ODSGD_LOCAL_SGD, 16, 2)[0::2] == (2, 2)   # the lowest count there is
+    assert plan(B.ODSGD_ENTRY_STEP, B.ODSGD_LOCAL_SGD, 16, 1)[0::2] == (2, 2)
+    # a CU whose LDS is so large that two workgroups cannot fill it: no request, no limit
+    assert B.odsgd_plan_residency(B.ODSGD_ENTRY_STEP, B.ODSGD_LOCAL_SGD, 16, 2, 512 * 1024, 1280, 64 * 1024)[1] == 0
+
+
+def test_residency_rejects_bad_arguments():
+    import ctypes as C
+    L = B.lib()
+    a, b, c = C.c_int(), C.c_size_t(), C.c_int()
+    bad = lambda *args: L.odsgd_plan_residency(*args, C.byref(a), C.byref(b), C.byref(c))
+    assert bad(9, 0, 8, 0, 163840, 1280, 65536) == B.ODSGD_EINVAL
+    assert bad(0, 7, 8, 0, 163840, 1280, 65536) == B.ODSGD_EINVAL
+    assert bad(0, 0, 0, 0, 163840, 1280, 65536) == B.ODSGD_EINVAL
+    assert bad(0, 0, 8, 0, 163840, 0, 65536) == B.ODSGD_EINVAL

@@ -136,6 +136,35 @@ def test_workloads_with_rules(name, rule, iters):
     eng.close()
 
 
+@pytest.mark.parametrize("rule", ["a", "m"])
+def test_state_that_is_only_4_byte_aligned_moves_the_tensor_to_the_32_bit_path(rule):
+    W, sizes = 3, [1000, 7, 4096]
+    st, arenas, gen = custom_state(sizes, W, seed=390)
+    for m in range(W):
+        for k, t in enumerate(st["u"][m]):
+            t.copy_(st["w"][k])
+    ms_arenas = [Arena(sizes, shift=1 + m) for m in range(W)]     # views 4, 8, 12 bytes past a 16-byte boundary
+    ms = [a.views for a in ms_arenas]
+    assert all(t.data_ptr() % 16 for r in ms for t in r)
+    for r in ms:
+        for t in r:
+            t.zero_()
+    hs = host_state(st)
+    ms_h = [to_host(r) for r in ms]
+    eng = make_engine(st)
+    hy = (0.05, 0.02, 0.9, 1e-3, 0.0)
+    oh = oracle_hyper(hy)
+    orule = install_rule(eng, rule, ms, ms_h)
+    for it in range(3):
+        eng.step(hy)
+        oracle.step(it, 0, hs["w"], hs["v"], hs["g"], hs["u"], rule=orule, **oh)
+        assert compare(st, hs, label="it %d" % it)[0] == 0 and compare_ms(ms, ms_h) == 0
+        regen_grads(st, gen, gstd=1e-2)
+        refresh_host_grads(st, hs)
+    assert arenas_intact(arenas) and all(a.intact() for a in ms_arenas)
+    eng.close()
+
+
 def test_rule_error_paths():
     n = 1024
     t = lambda: torch.zeros(n, device=DEV)
@@ -154,9 +183,10 @@ def test_rule_error_paths():
         shared = t()
         eng.set_local_rule(B.ODSGD_LOCAL_DCASGD_A, lam=2.0, mean_square=[[shared], [shared]])
     assert e.value.code == B.ODSGD_EALIAS
-    big = torch.zeros(n + 4, device=DEV)
-    with pytest.raises(B.OdsgdError) as e:                            # state not 16-byte aligned
-        eng.set_local_rule(B.ODSGD_LOCAL_DCASGD_A, lam=2.0, mean_square=[[big[1:n + 1]], [t()]])
+    big, other = torch.zeros(n + 4, device=DEV), t()
+    with pytest.raises(B.OdsgdError) as e:                            # state not even 4-byte aligned
+        B.odsgd_set_local_rule(eng.handle, B.ODSGD_LOCAL_DCASGD_A, lam=2.0,
+                               state_ptrs=[[big.data_ptr() + 2], [other.data_ptr()]])
     assert e.value.code == B.ODSGD_EALIGN
     # a failed registration leaves the SGD rule in place and the engine usable
     eng.step((0.1, 0.1, 0.9, 0.0, 0.0))

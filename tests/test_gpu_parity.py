@@ -45,7 +45,10 @@ def test_hand_expanded_sequence_on_gpu(golden_w2):
 # ---------------------------------------------------------------------------
 # the five parameter sets, fused step, all outputs compared after every iteration
 # ---------------------------------------------------------------------------
-def run_workload(name, iterations, warmup=0, layout="separate"):
+def run_workload(name, iterations, warmup=0, layout="separate", every_output=None):
+    """every_output(it) -> compare w, momentum and all local weights after iteration `it`
+    (default: always); otherwise only w and momentum, which carry the accumulated state --
+    the local weights are rewritten from scratch by every iteration."""
     w = wl.WORKLOADS[name]
     say("workload %s: K=%d N=%d W=%d iterations=%d warmup=%d" %
         (name, len(w.tensors), wl.total_params(w), w.num_workers, iterations, warmup))
@@ -60,11 +63,18 @@ def run_workload(name, iterations, warmup=0, layout="separate"):
         refresh_host_grads(st, hs)
         eng.step(hy)
         oracle.step(it, warmup, hs["w"], hs["v"], hs["g"], hs["u"], **oh)
-        bad, worst = compare(st, hs, label="%s it %d" % (name, it))
+        what = ("w", "v", "u") if every_output is None or every_output(it) else ("w", "v")
+        bad, worst = compare(st, hs, what=what, label="%s it %d" % (name, it))
         total_bad += bad
+        say("  %s iteration %d of %d compared (%s)" % (name, it + 1, iterations, "+".join(what)))
     say("  %s: %d elements differ bitwise from the oracle" % (name, total_bad))
     eng.close()
     return total_bad
+
+
+def ends_only(iterations):
+    """All outputs after the first two and the last iteration; w and momentum after every one."""
+    return lambda it: it < 2 or it == iterations - 1
 
 
 def test_lenet5_full_run():
@@ -75,16 +85,19 @@ def test_resnet20_full_run_heavy_tailed_gradients():
     assert run_workload("resnet20", wl.WORKLOADS["resnet20"].iterations) == 0
 
 
-def test_resnet50_full_size():
-    assert run_workload("resnet50", 3) == 0
+def test_resnet50_full_size_full_run():
+    n = wl.WORKLOADS["resnet50"].iterations
+    assert n == 50 and run_workload("resnet50", n, every_output=ends_only(n)) == 0
 
 
-def test_alexnet_full_size():
-    assert run_workload("alexnet", 2) == 0
+def test_alexnet_full_size_full_run():
+    n = wl.WORKLOADS["alexnet"].iterations
+    assert n == 20 and run_workload("alexnet", n, every_output=ends_only(n)) == 0
 
 
-def test_vgg16_full_size_with_exact_zero_gradients():
-    assert run_workload("vgg16", 2) == 0
+def test_vgg16_full_size_full_run_with_exact_zero_gradients():
+    n = wl.WORKLOADS["vgg16"].iterations
+    assert n == 10 and run_workload("vgg16", n, every_output=ends_only(n)) == 0
 
 
 def test_resnet20_with_warmup_schedule():
@@ -157,6 +170,64 @@ def test_worker_counts_ragged_sizes_all_entry_points(W):
     eng.close()
 
 
+BLOCKY = [16384 * 3 + 77, 5, 16384, 16383, 20000, 16384 * 2, 1, 70000]
+
+
+@pytest.mark.parametrize("block_phase", [0, 512, 1040, 65536 - 16, 32768 + 256])
+@pytest.mark.parametrize("W", [2, 8, 16, 5])
+def test_two_half_tiles_all_entry_points(W, block_phase):
+    """Every array of a tensor at the same offset from a 64 KiB boundary: the blocks inside
+    take two-half tiles, the pieces before and after them contiguous ones; the oracle knows
+    nothing of either."""
+    say("W=%d block_phase=%d sizes=%s" % (W, block_phase, BLOCKY))
+    st, arenas, gen = custom_state(BLOCKY, W, seed=600 + W, block_phase=block_phase)
+    ptrs = lambda lst: [t.data_ptr() for t in lst]
+    rows, chunks = B.odsgd_plan_host(BLOCKY, ptrs(st["w"]), ptrs(st["v"]), [ptrs(r) for r in st["g"]],
+                                     [ptrs(r) for r in st["u"]], W)
+    assert sum(1 for c in chunks if c[4]) >= 64 * 5, "expected two-half tiles in this layout"
+    hs = host_state(st)
+    eng = make_engine(st)
+    hy = (0.05, 0.02, 0.9, 1e-3, 0.0)
+    oh = oracle_hyper(hy)
+    eng.step(hy)
+    oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], **oh)
+    assert compare(st, hs, label="fused")[0] == 0
+    regen_grads(st, gen)
+    refresh_host_grads(st, hs)
+    eng.local_update(-1, hy)
+    eng.global_update(hy)
+    oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], **oh)
+    assert compare(st, hs, label="local(all)+global")[0] == 0
+    regen_grads(st, gen)
+    refresh_host_grads(st, hs)
+    eng.local_update(W // 2, hy)
+    oracle.local_update(hs["w"], hs["g"], hs["u"], oh["local_lr"], oh["weight_decay"], worker=W // 2)
+    assert compare(st, hs, label="local(m)")[0] == 0
+    eng.ssgd_step(hy)
+    oracle.ssgd_step(hs["w"], hs["v"], hs["g"], hs["u"], oh["lr"], oh["momentum"],
+                     oh["weight_decay"], oh["grad_scale"])
+    assert compare(st, hs, label="ssgd")[0] == 0
+    assert arenas_intact(arenas)
+    eng.close()
+
+
+def test_probe_streams_moves_the_same_arrays_and_changes_nothing_else():
+    W = 8
+    st, arenas, gen = custom_state(BLOCKY, W, seed=650, block_phase=0)
+    before = host_state(st)
+    eng = make_engine(st)
+    eng.probe_streams()
+    torch.cuda.synchronize()
+    after = host_state(st)
+    for k in range(len(BLOCKY)):
+        assert same_bits(after["w"][k], before["w"][k]) and same_bits(after["v"][k], before["v"][k])
+        for m in range(W):
+            assert same_bits(after["g"][m][k], before["g"][m][k])
+            assert same_bits(after["u"][m][k], before["g"][m][k])   # local weights received the gradients
+    assert eng.iteration == 0 and arenas_intact(arenas)
+    eng.close()
+
+
 @pytest.mark.parametrize("shifts", [{"w": 1}, {"g": 2}, {"u": 3}, {"w": 1, "v": 1, "g": 1, "u": 1}])
 def test_pointers_only_4_byte_aligned_take_the_scalar_path(shifts):
     say("shifts=%s" % shifts)
@@ -181,20 +252,20 @@ def test_pointers_only_4_byte_aligned_take_the_scalar_path(shifts):
     eng.close()
 
 
-@pytest.mark.parametrize("env", [{"ODSGD_CHUNK_ELEMS": "1024"}, {"ODSGD_CHUNK_ELEMS": "65536"},
+@pytest.mark.parametrize("env", [{"ODSGD_PAIR_BIT": "0"}, {"ODSGD_PAIR_BIT": "12"}, {"ODSGD_PAIR_BIT": "17"},
                                  {"ODSGD_BLOCKS_PER_CU": "1"}, {"ODSGD_BLOCKS_PER_CU": "8"},
-                                 {"ODSGD_CHUNK_ELEMS": "2048", "ODSGD_BLOCKS_PER_CU": "2"},
+                                 {"ODSGD_PAIR_BIT": "0", "ODSGD_BLOCKS_PER_CU": "2"},
                                  {"ODSGD_WAVES_PER_CU": "-1"}, {"ODSGD_WAVES_PER_CU": "2"},
-                                 {"ODSGD_WAVES_PER_CU": "7", "ODSGD_CHUNK_ELEMS": "512"}])
+                                 {"ODSGD_WAVES_PER_CU": "7", "ODSGD_PAIR_BIT": "13"}])
 def test_launch_shape_does_not_change_results(env):
-    """Chunk size and grid size are tuning only: outputs are bitwise the same."""
+    """Tile shape, grid size and residency are tuning only: outputs are bitwise the same."""
     say("env=%s" % env)
     sizes = RAGGED + [300000]
     W = 8
     old = {k: os.environ.get(k) for k in env}
     os.environ.update(env)
     try:
-        st, arenas, gen = custom_state(sizes, W, seed=11)
+        st, arenas, gen = custom_state(sizes, W, seed=11, block_phase=528)
         hs = host_state(st)
         eng = make_engine(st)
     finally:
