@@ -4,17 +4,24 @@
 A "step" is one pass of the whole update path over the resident state: W-way
 gradient reduce + global momentum-SGD update + W local compensated updates, in
 one launch (odsgd_step).  Inputs (weights, momentum, W gradient buffers) are in
-HBM before the timed region starts.
+HBM before the timed region starts.  The headline workload is the largest
+parameter set, VGG-16-shaped with W = 16 (19.9 GB moved per step).
 
 Prints ONE JSON line:
-  value      params updated per second (N / step time), whole job on the one GPU
-  roofline   algorithmic bytes 8*(W+2)*N per launch / mean kernel duration
-             (HIP events on the launch stream) against the 8 TB/s HBM peak
-  cpu_baseline  the CPU oracle timed on this host on a bounded sample
+  value        params updated per second (N / wall time per step) on the headline set
+  roofline     the headline set: algorithmic bytes 8*(W+2)*N per launch / mean
+               kernel duration (HIP events on the launch stream, same K steps)
+               against the 8 TB/s HBM peak
+  roofline_by_workload   the same for each of the three roofline sets, back-to-back
+               and with a cold last-level cache, and which of the two is the HBM rate
+  cpu_baseline the CPU oracle timed on this host on a bounded sample
 """
 import argparse
+import hashlib
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -22,10 +29,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-
-# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE and WRITE_SIZE runs,
-# scaled by the same counters on the 1 GiB copy probe); see profiles/.  Absent = not measured.
-MEASURED_TRAFFIC_BYTES = {"resnet50": 2.0576e9, "vgg16": 1.9992e10}
+LAST_LEVEL_CACHE_BYTES = 256 << 20   # MI355X Infinity Cache
+ROOFLINE_SETS = ("vgg16", "resnet50", "alexnet")
+KERNEL_SOURCE = os.path.join(ROOT, "paper_2005_06728_amd", "csrc", "odsgd.hip")
 
 PAPER_CONTEXT = {
     "note": "the paper reports end-to-end training speed only, never the update path; other hardware, context only",
@@ -39,77 +45,163 @@ def algorithmic_bytes(n_params, W):
     return 8 * (W + 2) * n_params
 
 
-def time_gpu(wl_mod, B, torch, name, steps, warmup, layout="separate"):
-    """layout="separate": one torch allocation per tensor per role (what the headline uses);
-    layout="arena": each role packed into one flat bucket with tile-aligned tensor starts."""
-    w = wl_mod.WORKLOADS[name]
-    dev = "cuda:0"
-    st = wl_mod.allocate(w, dev, layout=layout, skew_bytes=0, align_elems=256)
-    wl_mod.fill_all_grads_(st, w, 0)
-    eng = B.Engine(st["w"], st["v"], st["g"], st["u"])
-    hy = B.odsgd_hyper(*w.hyper)
+def measured_traffic(workload):
+    """HBM bytes per launch from the rocprofv3 counter summary under profiles/, if that summary
+    was made from the kernel source this run times; otherwise null with the reason."""
+    rel = os.path.join("profiles", "odsgd_step_%s.md" % workload)
+    path = os.path.join(ROOT, rel)
+    if not os.path.exists(path):
+        return None, "no counter summary %s" % rel
+    text = open(path).read()
+    m = re.search(r"measured HBM traffic per launch: ([0-9.eE+]+) bytes", text)
+    sha = re.search(r"kernel source sha256: ([0-9a-f]{64})", text)
+    if not m or not sha:
+        return None, "%s holds no traffic figure" % rel
+    now = hashlib.sha256(open(KERNEL_SOURCE, "rb").read()).hexdigest()
+    if sha.group(1) != now:
+        return None, "%s was measured on an older kernel source (sha256 %s...)" % (rel, sha.group(1)[:12])
+    return float(m.group(1)), "%s: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, scaled by the same counters on " \
+                              "the 1 GiB copy probe; same kernel source (sha256 %s...)" % (rel, now[:12])
+
+
+def launch_stats(ms, nbytes):
+    mean = sum(ms) / len(ms)
+    med = statistics.median(ms)
+    return {"launches": len(ms), "kernel_ms_mean": mean, "kernel_ms_median": med, "kernel_ms_min": min(ms),
+            "achieved": nbytes / (mean * 1e-3) / 1e9, "frac": nbytes / (mean * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+            "frac_at_median": nbytes / (med * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+
+
+def timed_launches(torch, fn, steps, warmup):
+    """K back-to-back calls bracketed by synchronisation; HIP events on the launch stream around every call.
+    Returns (wall ms per step, [kernel ms])."""
     stream = torch.cuda.current_stream()
     for _ in range(warmup):
-        eng.step(hy, stream)
+        fn(stream)
     events = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     events[0].record(stream)
     for i in range(steps):
-        eng.step(hy, stream)
+        fn(stream)
         events[i + 1].record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    per_launch_ms = [events[i].elapsed_time(events[i + 1]) for i in range(steps)]
+    return (t1 - t0) * 1e3 / steps, [events[i].elapsed_time(events[i + 1]) for i in range(steps)]
+
+
+def cold_launches(torch, fn, steps=10, warmup=2):
+    """Each launch timed alone after 2 GiB of unrelated device traffic, which evicts whatever
+    the previous step left in the last-level cache: what a step sees when forward/backward
+    ran in between."""
+    stream = torch.cuda.current_stream()
+    a, b = torch.zeros(1 << 28, device="cuda:0"), torch.zeros(1 << 28, device="cuda:0")
+    out = []
+    for i in range(warmup + steps):
+        b.copy_(a)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        fn(stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        if i >= warmup:
+            out.append(e0.elapsed_time(e1))
+    return out
+
+
+def measure_workload(wl_mod, B, torch, name, steps, warmup, layout="separate", cold=True, probe=True):
+    """Fused step on one parameter set: back-to-back, cold cache, and the arithmetic-free
+    probe of the same access shape.  layout="separate": one torch allocation per tensor per
+    role; layout="arena": each role packed into one flat bucket with tile-aligned tensor starts."""
+    w = wl_mod.WORKLOADS[name]
+    st = wl_mod.allocate(w, "cuda:0", layout=layout, skew_bytes=0, align_elems=256)
+    wl_mod.fill_all_grads_(st, w, 0)
+    eng = B.Engine(st["w"], st["v"], st["g"], st["u"])
+    hy = B.odsgd_hyper(*w.hyper)
+    N, W = wl_mod.total_params(w), w.num_workers
+    nbytes = algorithmic_bytes(N, W)
+    wall_ms, ms = timed_launches(torch, lambda s: eng.step(hy, s), steps, warmup)
+    fits = 8 * N <= LAST_LEVEL_CACHE_BYTES
+    r = {"workload": name, "tensors": len(w.tensors), "params": N, "workers": W,
+         "algorithmic_bytes_per_launch": nbytes, "ms_per_step": wall_ms, "params_per_s": N / (wall_ms * 1e-3),
+         "back_to_back": launch_stats(ms, nbytes),
+         "w_and_momentum_bytes": 8 * N, "w_and_momentum_fit_last_level_cache": fits}
+    if cold:
+        r["cold_cache"] = launch_stats(cold_launches(torch, lambda s: eng.step(hy, s)), nbytes)
+        r["cold_cache"]["how"] = "2 GiB device copy between launches, each launch timed alone"
+    # which figure is an HBM rate: back-to-back steps re-read w and momentum (loaded through the
+    # cache) from the 256 MB last-level cache when they fit, so only the cold figure is one then
+    r["hbm_frac"] = r["cold_cache"]["frac"] if (fits and cold) else r["back_to_back"]["frac"]
+    r["hbm_frac_is"] = "cold_cache" if (fits and cold) else "back_to_back"
+    if probe:
+        _, pms = timed_launches(torch, lambda s: eng.probe_streams(s), max(5, min(steps, 20)), 2)
+        r["same_shape_copy_probe"] = launch_stats(pms, nbytes)
+        r["frac_of_same_shape_copy_probe"] = r["back_to_back"]["achieved"] / r["same_shape_copy_probe"]["achieved"]
     eng.close()
-    N = wl_mod.total_params(w)
-    return {
-        "workload": name, "tensors": len(w.tensors), "params": N, "workers": w.num_workers,
-        "ms_per_step": (t1 - t0) * 1e3 / steps,
-        "kernel_ms_mean": sum(per_launch_ms) / steps,
-        "kernel_ms_min": min(per_launch_ms),
-        "bytes_per_step": algorithmic_bytes(N, w.num_workers),
-    }, st
+    return r, st
 
 
-def time_entry_points(wl_mod, B, torch, name, st, steps=20, warmup=3):
-    """The other entry points and local updaters on the same resident state, each
-    against its own algorithmic bytes per parameter."""
+def time_entry_points(wl_mod, B, torch, name, st, steps=15, warmup=3):
+    """The other entry points and local updaters on the same resident state, each against its
+    own algorithmic bytes per parameter, and the two halves of an iteration run on two streams."""
     w = wl_mod.WORKLOADS[name]
     W, N = w.num_workers, wl_mod.total_params(w)
     hy = B.odsgd_hyper(*w.hyper)
-    stream = torch.cuda.current_stream()
-    ms = [[torch.zeros_like(t) for t in st["w"]] for _ in range(W)]
+    state = [[torch.zeros_like(t) for t in st["w"]] for _ in range(W)]
     eng = B.Engine(st["w"], st["v"], st["g"], st["u"])
     cases = [
-        ("odsgd_local_update(-1) sgd", 4 * (2 * W + 1), None, lambda: eng.local_update(-1, hy, stream)),
-        ("odsgd_global_update", 4 * (W + 4), None, lambda: eng.global_update(hy, stream)),
-        ("odsgd_ssgd_step", 8 * (W + 2), None, lambda: eng.ssgd_step(hy, stream)),
+        ("odsgd_local_update(-1) sgd", 4 * (2 * W + 1), None, lambda s: eng.local_update(-1, hy, s)),
+        ("odsgd_global_update", 4 * (W + 4), None, lambda s: eng.global_update(hy, s)),
+        ("odsgd_ssgd_step", 8 * (W + 2), None, lambda s: eng.ssgd_step(hy, s)),
         ("odsgd_step dcasgd_c", 4 * (3 * W + 4), (B.ODSGD_LOCAL_DCASGD_C, 0.04, 0.0, 0.0, None),
-         lambda: eng.step(hy, stream)),
-        ("odsgd_step dcasgd_a", 4 * (5 * W + 4), (B.ODSGD_LOCAL_DCASGD_A, 2.0, 0.95, 1e-7, ms),
-         lambda: eng.step(hy, stream)),
-        ("odsgd_step local momentum", 4 * (4 * W + 4), (B.ODSGD_LOCAL_SGD_MOMENTUM, 0.0, 0.0, 0.0, ms),
-         lambda: eng.step(hy, stream)),
+         lambda s: eng.step(hy, s)),
+        ("odsgd_step dcasgd_a", 4 * (5 * W + 4), (B.ODSGD_LOCAL_DCASGD_A, 2.0, 0.95, 1e-7, state),
+         lambda s: eng.step(hy, s)),
+        ("odsgd_step local momentum", 4 * (4 * W + 4), (B.ODSGD_LOCAL_SGD_MOMENTUM, 0.0, 0.0, 0.0, state),
+         lambda s: eng.step(hy, s)),
     ]
     out = {}
     for label, bpp, rule, fn in cases:
         if rule is not None:
             eng.set_local_rule(rule[0], lam=rule[1], ms_decay=rule[2], epsilon=rule[3], mean_square=rule[4],
                                local_momentum=0.9)
-        for _ in range(warmup):
-            fn()
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        _, ms = timed_launches(torch, fn, steps, warmup)
+        out[label] = dict(launch_stats(ms, bpp * N), bytes_per_param=bpp)
+    eng.close()
+    del state
+
+    # split path: serial on one stream, then the two kernels on two streams at once
+    # (out-of-place global update), each iteration against the split total 4*(3W+5) B/param
+    eng = B.Engine(st["w"], st["v"], st["g"], st["u"])
+    bpp = 4 * (3 * W + 5)
+
+    def serial(s):
+        eng.local_update(-1, hy, s)
+        eng.global_update(hy, s)
+
+    _, ms = timed_launches(torch, serial, steps, warmup)
+    out["split, one stream: local_update(-1) then global_update"] = dict(launch_stats(ms, bpp * N), bytes_per_param=bpp)
+    alt_w = [torch.empty_like(t) for t in st["w"]]
+    alt_v = [torch.empty_like(t) for t in st["v"]]
+    eng.set_double_buffer(alt_w, alt_v)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    main = torch.cuda.current_stream()
+
+    def concurrent(s):
+        sa.wait_stream(s)
+        sb.wait_stream(s)
+        eng.local_update(-1, hy, sa)
+        eng.global_update(hy, sb)
+        s.wait_stream(sa)
+        s.wait_stream(sb)
+
+    _, ms = timed_launches(torch, concurrent, steps, warmup)
+    out["split, two streams at once (out-of-place global update)"] = dict(launch_stats(ms, bpp * N),
+                                                                          bytes_per_param=bpp)
+    torch.cuda.synchronize()
+    if eng.current_buffers:   # leave the current weights where the caller's tensors are
+        eng.global_update(hy, main)
         torch.cuda.synchronize()
-        ev[0].record(stream)
-        for _ in range(steps):
-            fn()
-        ev[1].record(stream)
-        torch.cuda.synchronize()
-        ms_launch = ev[0].elapsed_time(ev[1]) / steps
-        gbps = bpp * N / (ms_launch * 1e-3) / 1e9
-        out[label] = {"bytes_per_param": bpp, "kernel_ms_mean": ms_launch, "hbm_gbps": gbps,
-                      "hbm_frac": gbps / HBM_PEAK_GBPS}
     eng.close()
     return out
 
@@ -156,63 +248,21 @@ def time_small(wl_mod, B, torch, name, steps=200, graph_len=20):
     return out
 
 
-def time_cold(wl_mod, B, torch, name, st, steps=10, warmup=2):
-    """The fused step with a cold last-level cache: 2 GiB of unrelated traffic between
-    launches, each launch timed on its own.  In the back-to-back loop the arrays
-    that the next step reads again (w and momentum) can stay in the 256 MB
-    Infinity Cache when they fit; with other work between steps they would not."""
-    w = wl_mod.WORKLOADS[name]
-    eng = B.Engine(st["w"], st["v"], st["g"], st["u"])
-    hy = B.odsgd_hyper(*w.hyper)
-    stream = torch.cuda.current_stream()
-    a, b = torch.zeros(1 << 28, device="cuda:0"), torch.zeros(1 << 28, device="cuda:0")
-    tot = 0.0
-    for i in range(warmup + steps):
-        b.copy_(a)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        eng.step(hy, stream)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        if i >= warmup:
-            tot += e0.elapsed_time(e1)
-    eng.close()
-    ms = tot / steps
-    gbps = algorithmic_bytes(wl_mod.total_params(w), w.num_workers) / (ms * 1e-3) / 1e9
-    return {"kernel_ms_mean": ms, "achieved": gbps, "frac": gbps / HBM_PEAK_GBPS,
-            "how": "2 GiB device copy between launches, each launch timed alone"}
-
-
 def time_copy_probe(B, torch, steps, warmup, gib=1.0):
-    """Plain copy of `gib` GiB (read) + `gib` GiB (write) per launch, same tile shape as the update kernel."""
+    """Plain copy of `gib` GiB (read) + `gib` GiB (write) per launch, one contiguous 1 KiB tile per wavefront."""
     n = int(gib * (1 << 30)) // 4
     src = torch.empty(n, dtype=torch.float32, device="cuda:0").normal_()
     dst = torch.empty_like(src)
-    stream = torch.cuda.current_stream()
-    for _ in range(warmup):
-        B.odsgd_probe_copy(dst, src, stream)
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-    torch.cuda.synchronize()
-    ev[0].record(stream)
-    for _ in range(steps):
-        B.odsgd_probe_copy(dst, src, stream)
-    ev[1].record(stream)
-    torch.cuda.synchronize()
-    ms = ev[0].elapsed_time(ev[1]) / steps
+    _, ms = timed_launches(torch, lambda s: B.odsgd_probe_copy(dst, src, s), steps, warmup)
     assert torch.equal(dst, src)
-    return {"bytes_per_launch": 8 * n, "kernel_ms_mean": ms, "gbps": 8 * n / (ms * 1e-3) / 1e9}
+    mean = sum(ms) / len(ms)
+    return {"bytes_per_launch": 8 * n, "kernel_ms_mean": mean, "gbps": 8 * n / (mean * 1e-3) / 1e9}
 
 
-def summarize(r):
-    out = dict(r)
-    out["params_per_s"] = r["params"] / (r["ms_per_step"] * 1e-3)
-    out["hbm_gbps"] = r["bytes_per_step"] / (r["kernel_ms_mean"] * 1e-3) / 1e9
-    out["hbm_frac"] = out["hbm_gbps"] / HBM_PEAK_GBPS
-    return out
-
-
-def cpu_baseline(wl_mod, name, st, budget_s=12.0):
-    """Time the oracle, as it stands, single-threaded on host copies of the same state."""
+def cpu_baseline(wl_mod, name, st, iterations=3):
+    """Time the oracle, as it stands, on host copies of the same state: single thread (the
+    reference definition), then the same routine over a static split of the flat element
+    range, one thread per host core."""
     import numpy as np
     from oracle import odsgd_oracle as oracle
     w = wl_mod.WORKLOADS[name]
@@ -220,44 +270,38 @@ def cpu_baseline(wl_mod, name, st, budget_s=12.0):
     hs["g"] = [[t.cpu().numpy() for t in r] for r in st["g"]]
     hs["u"] = [[t.cpu().numpy() for t in r] for r in st["u"]]
     hy = [float(np.float32(x)) for x in w.hyper]
-    N = wl_mod.total_params(w)
+    N, W = wl_mod.total_params(w), w.num_workers
 
-    def one():
+    def timed(fn):
         t0 = time.perf_counter()
-        oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], *hy)
+        fn()
         return time.perf_counter() - t0
 
-    one()  # page in
-    t_first = one()
-    reps = max(1, min(50, int(budget_s / max(t_first, 1e-6))))
-    times = [one() for _ in range(reps)]
-    t = sum(times) / reps
-
-    # the same oracle loop over disjoint element ranges, one thread per host core
-    from concurrent.futures import ThreadPoolExecutor
+    single = lambda: oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], *hy)
+    timed(single)  # page in
+    times = [timed(single) for _ in range(iterations)]
+    t = statistics.median(times)
     threads = max(1, min(16, len(os.sched_getaffinity(0))))
-
-    def part(lst, j):
-        return [a[(a.shape[0] * j) // threads:(a.shape[0] * (j + 1)) // threads] for a in lst]
-
-    parts = [(part(hs["w"], j), part(hs["v"], j), [part(r, j) for r in hs["g"]], [part(r, j) for r in hs["u"]])
-             for j in range(threads)]
-
-    def all_cores():
-        t0 = time.perf_counter()
-        with ThreadPoolExecutor(threads) as ex:
-            list(ex.map(lambda p: oracle.od_step(p[0], p[1], p[2], p[3], *hy), parts))
-        return time.perf_counter() - t0
-
-    all_cores()
-    t_mt = min(all_cores() for _ in range(3))
+    multi = lambda: oracle.od_step_threads(hs["w"], hs["v"], hs["g"], hs["u"], *hy, threads=threads)
+    timed(multi)
+    times_mt = [timed(multi) for _ in range(max(3, iterations))]
+    t_mt = statistics.median(times_mt)
+    nbytes = algorithmic_bytes(N, W)
     return {"value": N / t, "unit": "params/s", "cores": 1, "kind": "oracle",
-            "sample": "%d full OD-SGD steps of the %s parameter set (N=%d, W=%d), single thread, %.2f s each"
-                      % (reps, name, N, w.num_workers, t),
-            "gbps": algorithmic_bytes(N, w.num_workers) / t / 1e9,
-            "all_cores": {"value": N / t_mt, "unit": "params/s", "cores": threads,
-                          "gbps": algorithmic_bytes(N, w.num_workers) / t_mt / 1e9,
-                          "sample": "same step, elements split statically over %d threads, best of 3" % threads}}
+            "sample": "%d full OD-SGD steps of the %s parameter set (N=%d, W=%d) after one untimed step, single "
+                      "thread, median %.2f s each" % (iterations, name, N, W, t),
+            "gbps": nbytes / t / 1e9,
+            "all_cores": {"value": N / t_mt, "unit": "params/s", "cores": threads, "gbps": nbytes / t_mt / 1e9,
+                          "speedup_over_one_core": t / t_mt,
+                          "sample": "same step, flat element range split statically over %d POSIX threads "
+                                    "(oracle/threads.c), median of %d" % (threads, len(times_mt))}}
+
+
+def brief(r):
+    keep = ("workload", "tensors", "params", "workers", "algorithmic_bytes_per_launch", "ms_per_step", "params_per_s",
+            "back_to_back", "cold_cache", "hbm_frac", "hbm_frac_is", "w_and_momentum_bytes",
+            "w_and_momentum_fit_last_level_cache", "same_shape_copy_probe", "frac_of_same_shape_copy_probe")
+    return {k: r[k] for k in keep if k in r}
 
 
 def main():
@@ -265,16 +309,19 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="resnet50")
-    ap.add_argument("--others", default="vgg16,alexnet",
-                    help="comma list of further workloads measured in the same run ('' for none)")
+    ap.add_argument("--workload", default="vgg16")
+    ap.add_argument("--others", default=None,
+                    help="comma list of further roofline sets measured in the same run (default: the other "
+                         "two of vgg16, resnet50, alexnet; '' for none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--headline-only", action="store_true",
-                    help="only the headline workload and the copy probe (what the rocprofv3 runs use): no "
-                         "other workloads, layouts, entry points, cold-cache or CPU measurements")
+                    help="only the headline workload's timed steps and the copy probe (what the rocprofv3 runs "
+                         "use): no other workloads, layouts, entry points, cold-cache or CPU measurements")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only the plain copy kernel of known traffic (counter calibration)")
     args = ap.parse_args()
+    if args.others is None:
+        args.others = ",".join(x for x in ROOFLINE_SETS if x != args.workload)
     if args.headline_only:
         args.others, args.no_cpu_baseline = "", True
     if args.gpus != 1:
@@ -294,69 +341,72 @@ def main():
         print(json.dumps({"copy_probe": r}))
         return
 
-    main_r, st = time_gpu(wl_mod, B, torch, args.workload, args.steps, args.warmup)
-    main_s = summarize(main_r)
-    cpu = None
-    if not args.no_cpu_baseline:
-        cpu = cpu_baseline(wl_mod, args.workload, st)
-    cold = None if args.headline_only else time_cold(wl_mod, B, torch, args.workload, st)
-    entry_points = {} if args.headline_only else time_entry_points(wl_mod, B, torch, args.workload, st)
+    full = not args.headline_only
+    head, st = measure_workload(wl_mod, B, torch, args.workload, args.steps, args.warmup, cold=full, probe=full)
+    cpu = None if args.no_cpu_baseline else cpu_baseline(wl_mod, args.workload, st)
+    by_workload = {args.workload: brief(head)}
+    entry_points = {}
+    if full:
+        entry_points[args.workload] = time_entry_points(wl_mod, B, torch, args.workload, st)
     del st
     torch.cuda.empty_cache()
 
-    others = {}
     for name in [x for x in args.others.split(",") if x and x != args.workload]:
-        r, st2 = time_gpu(wl_mod, B, torch, name, max(5, min(args.steps, 20)), args.warmup)
+        r, st2 = measure_workload(wl_mod, B, torch, name, max(5, min(args.steps, 30)), args.warmup)
+        by_workload[name] = brief(r)
+        if name == "resnet50":
+            entry_points[name] = time_entry_points(wl_mod, B, torch, name, st2)
         del st2
         torch.cuda.empty_cache()
-        s = summarize(r)
-        others[name] = {k: s[k] for k in ("params", "workers", "ms_per_step", "kernel_ms_mean",
-                                          "params_per_s", "hbm_gbps", "hbm_frac")}
+
     # the same fused step with every role packed into one flat bucket (the usual
     # gradient-bucket layout) instead of one allocation per tensor
     buckets = {}
-    for name in ([] if args.headline_only else
-                 [args.workload] + [x for x in args.others.split(",") if x and x != args.workload]):
-        r, st2 = time_gpu(wl_mod, B, torch, name, max(5, min(args.steps, 20)), args.warmup, layout="arena")
+    for name in ([] if not full else [args.workload] + [x for x in args.others.split(",") if x and x != args.workload]):
+        r, st2 = measure_workload(wl_mod, B, torch, name, max(5, min(args.steps, 20)), args.warmup, layout="arena",
+                                  cold=False, probe=False)
         del st2
         torch.cuda.empty_cache()
-        s = summarize(r)
-        buckets[name] = {k: s[k] for k in ("kernel_ms_mean", "hbm_gbps", "hbm_frac")}
+        buckets[name] = r["back_to_back"]
 
-    small = {} if args.headline_only else {n: time_small(wl_mod, B, torch, n) for n in ("lenet5", "resnet20")}
+    small = {n: time_small(wl_mod, B, torch, n) for n in ("lenet5", "resnet20")} if full else {}
     probe = time_copy_probe(B, torch, 20, 3)
     w = wl_mod.WORKLOADS[args.workload]
+    b2b = head["back_to_back"]
+    traffic, traffic_source = measured_traffic(args.workload)
     line = {
         "metric": "params updated/sec per OD-SGD step (and achieved HBM GB/s, see roofline)",
-        "value": main_s["params_per_s"],
+        "value": head["params_per_s"],
         "unit": "params/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": main_s["ms_per_step"],
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "%s-shaped parameter set" % args.workload, "tensors": main_s["tensors"],
-                   "params": main_s["params"], "workers": main_s["workers"],
+        "config": {"workload": "%s-shaped parameter set" % args.workload, "tensors": head["tensors"],
+                   "params": head["params"], "workers": head["workers"],
                    "hyper": dict(w.hyper._asdict()), "entry_point": "odsgd_step (fused, one launch)"},
-        "roofline": {"bound": "hbm", "achieved": main_s["hbm_gbps"], "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": main_s["hbm_frac"],
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload),
-                     "algorithmic_bytes_per_launch": main_s["bytes_per_step"],
-                     "kernel_ms_mean": main_s["kernel_ms_mean"], "kernel_ms_min": main_s["kernel_ms_min"],
+        "roofline": {"bound": "hbm", "achieved": b2b["achieved"], "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": b2b["frac"],
+                     "traffic": traffic, "traffic_source": traffic_source,
+                     "algorithmic_bytes_per_launch": head["algorithmic_bytes_per_launch"],
+                     "kernel_ms_mean": b2b["kernel_ms_mean"], "kernel_ms_median": b2b["kernel_ms_median"],
+                     "kernel_ms_min": b2b["kernel_ms_min"],
                      "plain_copy_gbps_same_box": probe["gbps"],
-                     "frac_of_plain_copy": main_s["hbm_gbps"] / probe["gbps"],
-                     "note": "timed region = K back-to-back steps; arrays the next step re-reads (w, momentum: "
-                             "%.0f MB) are loaded through the cache and can be served by the 256 MB last-level "
-                             "cache when they fit; roofline_cold_cache times the same launch after 2 GiB of "
-                             "unrelated traffic" % (8 * main_s["params"] / 1e6)},
-        "roofline_cold_cache": cold,
+                     "note": "timed region = the K back-to-back steps; mean kernel duration from HIP events around "
+                             "every launch on the launch stream. w and momentum of this set (%.0f MB) %s the 256 MB "
+                             "last-level cache, so this back-to-back figure %s an HBM rate; see "
+                             "roofline_by_workload for the cold-cache figures"
+                             % (head["w_and_momentum_bytes"] / 1e6,
+                                "fit" if head["w_and_momentum_fit_last_level_cache"] else "do not fit",
+                                "is cache-assisted, not" if head["w_and_momentum_fit_last_level_cache"] else "is")},
+        "roofline_by_workload": by_workload,
         "cpu_baseline": cpu,
         "other_entry_points": entry_points,
-        "other_workloads": others,
         "flat_bucket_layout": buckets,
         "launch_bound_workloads": small,
         "paper_context": PAPER_CONTEXT,

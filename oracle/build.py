@@ -33,5 +33,20 @@ def build(force=False, extra_cflags=(), lib=LIB, src=SRC):
     return lib
 
 
+THREADS_SRC = os.path.join(HERE, "threads.c")
+THREADS_LIB = os.path.join(HERE, "libodsgd_oracle_threads.so")
+
+
+def build_threads(force=False):
+    """The static multi-thread driver used by the benchmark's all-cores baseline (threads.c)."""
+    if (not force and os.path.exists(THREADS_LIB)
+            and os.path.getmtime(THREADS_LIB) >= os.path.getmtime(THREADS_SRC)):
+        return THREADS_LIB
+    subprocess.run(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-Wall", "-Wextra", "-Werror", THREADS_SRC,
+                    "-o", THREADS_LIB, "-lpthread"], check=True)
+    return THREADS_LIB
+
+
 if __name__ == "__main__":
     print(build(force="--force" in sys.argv))
+    print(build_threads(force="--force" in sys.argv))

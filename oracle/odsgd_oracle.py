@@ -189,3 +189,25 @@ def step(i, warmup_steps, w, v, g, u, lr, local_lr, momentum, weight_decay, grad
         else:
             raise ValueError(rule[0])
         global_update(w, v, g, lr, momentum, weight_decay, grad_scale)
+
+
+def od_step_threads(w, v, g, u, lr, local_lr, momentum, weight_decay, grad_scale=0.0, threads=1):
+    """od_step (float32 only) with the flat element range split statically over `threads`
+    POSIX threads by oracle/threads.c; every piece runs the same C routine as od_step."""
+    M, K = len(g), len(w)
+    f = ctypes.c_float
+    P = ctypes.POINTER(f)
+    for k in range(K):
+        n = w[k].shape[0]
+        _check([w[k], v[k]] + [g[m][k] for m in range(M)] + [u[m][k] for m in range(M)], np.dtype(np.float32), n)
+    tl = ctypes.CDLL(_build.build_threads())
+    fn = lib().odsgd_oracle_od_step_f32
+    numel = (ctypes.c_int64 * K)(*[a.shape[0] for a in w])
+    flat = lambda rows: _ptr_array([rows[m][k] for m in range(M) for k in range(K)], f)
+    tl.odsgd_oracle_threads_od_step_f32.restype = ctypes.c_int
+    rc = tl.odsgd_oracle_threads_od_step_f32(
+        ctypes.cast(fn, ctypes.c_void_p), ctypes.c_int(threads), ctypes.c_int(K), numel,
+        _ptr_array(w, f), _ptr_array(v, f), flat(g), flat(u), ctypes.c_int(M),
+        f(lr), f(local_lr), f(momentum), f(weight_decay), f(grad_scale))
+    if rc != 0:
+        raise RuntimeError("odsgd_oracle_threads_od_step_f32 failed")

@@ -81,8 +81,7 @@ namespace {
 #endif
 #define ODSGD_BLOCK 64  // one wavefront per workgroup
 #ifndef ODSGD_INFLIGHT_MEMOPS_PER_CU
-// target of (resident wavefronts per CU) x (128-bit loads + stores per lane per
-// tile); measured optimum 100-120 for every entry point and worker count tried
+// target of (resident wavefronts per CU) x (arrays a launch streams through)
 #define ODSGD_INFLIGHT_MEMOPS_PER_CU 110
 #endif
 
@@ -854,35 +853,37 @@ KernelFn pick_kernel(int mode, int rule, int wcount)
 // residency: how many one-wavefront workgroups a CU should hold, and the dynamic
 // LDS request that makes it so
 // ---------------------------------------------------------------------------
-// 128-bit loads + stores one lane issues per tile
-int memops_per_tile(int mode, int rule, int wcount)
+// distinct arrays a launch streams through (an array updated in place counts once)
+int arrays_per_tile(int mode, int rule, int wcount)
 {
-    int loads = (mode == MODE_LOCAL) ? wcount + 1 : wcount + 2;
-    int stores = (mode == MODE_GLOBAL) ? 2 : (mode == MODE_LOCAL) ? wcount : wcount + 2;
-    if (mode == MODE_OD || mode == MODE_LOCAL) {
-        if (rule == RULE_DCC || rule == RULE_DCA)
-            loads += wcount;  // previous local weights
-        if (rule == RULE_DCA || rule == RULE_MOM) {
-            loads += wcount;   // per-worker state in ...
-            stores += wcount;  // ... and out
-        }
-    }
-    return loads + stores;
+    int arrays = 1 + wcount;  // w and the gradients
+    if (mode != MODE_LOCAL)
+        ++arrays;  // momentum
+    if (mode != MODE_GLOBAL)
+        arrays += wcount;  // local weights
+    if ((mode == MODE_OD || mode == MODE_LOCAL) && (rule == RULE_DCA || rule == RULE_MOM))
+        arrays += wcount;  // per-worker state
+    return arrays;
 }
 
 // Resident wavefronts per CU wanted for a launch; 0 = no cap (full occupancy).
+// Measured on MI355X for every entry point and rule at W = 8 and W = 16: the
+// best residency is the one that keeps (wavefronts per CU) x (arrays) near
+// ODSGD_INFLIGHT_MEMOPS_PER_CU, i.e. the chip-wide window of open 1 KiB tiles
+// about constant -- 3 wavefronts for the 36 arrays of the fused step at W = 16,
+// 6 for the 20 arrays at W = 8.
 int wanted_waves(int mode, int rule, int wcount, int override_waves)
 {
     if (override_waves < 0)
         return 0;
     int waves = override_waves;
     if (waves == 0) {
-        const int ops = memops_per_tile(mode, rule, wcount);
-        waves = (ODSGD_INFLIGHT_MEMOPS_PER_CU + ops / 2) / ops;  // nearest integer
+        const int arrays = arrays_per_tile(mode, rule, wcount);
+        waves = (ODSGD_INFLIGHT_MEMOPS_PER_CU + arrays / 2) / arrays;  // nearest integer
         // the adaptive rule spends a correctly rounded sqrt and divide per element and
-        // worker: more wavefronts are needed to hide that arithmetic
+        // worker: at least one wavefront per SIMD and one more to hide that arithmetic
         if ((mode == MODE_OD || mode == MODE_LOCAL) && rule == RULE_DCA)
-            waves = std::max(5, (170 + ops / 2) / ops);
+            waves = std::max(5, waves);
         if (waves > 16)
             return 0;  // few streams: full occupancy is best
     }

@@ -433,3 +433,21 @@ def test_empty_tensor_is_a_no_op():
     u = [[np.zeros(0, F32), np.zeros(2, F32)]]
     oracle.od_step(w, v, g, u, 0.5, 0.25, 0.0, 0.0, 1.0)
     assert w[1].tolist() == [0.5, 0.5] and u[0][1].tolist() == [0.75, 0.75]
+
+
+def test_static_thread_split_is_the_single_thread_oracle_bit_for_bit():
+    """oracle/threads.c only cuts the flat element range into contiguous parts and calls the
+    oracle's own routine on each: any thread count must reproduce od_step exactly."""
+    rng = np.random.default_rng(11)
+    sizes = [5, 1000, 0, 77777, 3, 1]
+    M = 3
+    mk = lambda: [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    w, v, g, u = mk(), mk(), [mk() for _ in range(M)], [mk() for _ in range(M)]
+    ref = ([a.copy() for a in w], [a.copy() for a in v], [[a.copy() for a in r] for r in u])
+    oracle.od_step(ref[0], ref[1], g, ref[2], 0.1, 0.05, 0.9, 1e-3, 0.0)
+    for threads in (1, 2, 7, 16, 200):
+        w2, v2, u2 = [a.copy() for a in w], [a.copy() for a in v], [[a.copy() for a in r] for r in u]
+        oracle.od_step_threads(w2, v2, g, u2, 0.1, 0.05, 0.9, 1e-3, 0.0, threads=threads)
+        assert all(same_bits(a, b) for a, b in zip(w2, ref[0]))
+        assert all(same_bits(a, b) for a, b in zip(v2, ref[1]))
+        assert all(same_bits(a, b) for r, s in zip(u2, ref[2]) for a, b in zip(r, s))
