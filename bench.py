@@ -317,6 +317,8 @@ def main():
     ap.add_argument("--headline-only", action="store_true",
                     help="only the headline workload's timed steps and the copy probe (what the rocprofv3 runs "
                          "use): no other workloads, layouts, entry points, cold-cache or CPU measurements")
+    ap.add_argument("--with-cold", action="store_true",
+                    help="with --headline-only: also time the headline workload with a cold last-level cache")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run only the plain copy kernel of known traffic (counter calibration)")
     args = ap.parse_args()
@@ -342,7 +344,8 @@ def main():
         return
 
     full = not args.headline_only
-    head, st = measure_workload(wl_mod, B, torch, args.workload, args.steps, args.warmup, cold=full, probe=full)
+    head, st = measure_workload(wl_mod, B, torch, args.workload, args.steps, args.warmup,
+                                cold=full or args.with_cold, probe=full)
     cpu = None if args.no_cpu_baseline else cpu_baseline(wl_mod, args.workload, st)
     by_workload = {args.workload: brief(head)}
     entry_points = {}
