@@ -323,6 +323,9 @@ __device__ __forceinline__ void local_one(T w0, T gm, T r, T u_old, T st_old, ui
 // live at any time to two groups of operands and two groups of pointers instead
 // of all W of them: without it the W = 16 variants need more scalar registers
 // for pointers than exist, and the adaptive rule more than 230 vector registers.
+// (Fencing the groups off from one another with scheduling barriers removes the
+// few scalar spills the stateful rules keep at W >= 12, but was measured 1 %
+// slower, so the scheduler is left free.)
 // The gradient sum is accumulated as the groups go by, in ascending worker
 // order, so the result is the same left-to-right sum as before.
 // ---------------------------------------------------------------------------
@@ -870,8 +873,8 @@ int arrays_per_tile(int mode, int rule, int wcount)
 // Measured on MI355X for every entry point and rule at W = 8 and W = 16: the
 // best residency is the one that keeps (wavefronts per CU) x (arrays) near
 // ODSGD_INFLIGHT_MEMOPS_PER_CU, i.e. the chip-wide window of open 1 KiB tiles
-// about constant -- 3 wavefronts for the 36 arrays of the fused step at W = 16,
-// 6 for the 20 arrays at W = 8.
+// about constant -- 3 wavefronts for the 34 arrays of the fused step at W = 16,
+// 6 for the 18 arrays at W = 8.
 int wanted_waves(int mode, int rule, int wcount, int override_waves)
 {
     if (override_waves < 0)
