@@ -335,7 +335,7 @@ constexpr int group_size()
     constexpr bool local_rule = (MODE == MODE_OD || MODE == MODE_LOCAL);
     if (local_rule && RULE != RULE_SGD)
         return W_T >= 8 ? 4 : W_T;  // 2 or 3 loads and 1 or 2 stores per worker
-    return W_T >= 16 ? 8 : W_T;     // 1 load and at most 1 store per worker
+    return W_T > 12 ? 8 : W_T;      // 1 load and at most 1 store per worker
 }
 
 template <int W_T, int MODE, int RULE, typename T>
@@ -346,8 +346,7 @@ __device__ __forceinline__ void apply_fixed(ptr_table_t row, const KernelArgs &a
     constexpr bool need_u_old = local_rule && (RULE == RULE_DCC || RULE == RULE_DCA);
     constexpr bool need_state = local_rule && (RULE == RULE_DCA || RULE == RULE_MOM);  // per-worker state
     constexpr int G = group_size<W_T, MODE, RULE>();
-    constexpr int NG = W_T / G;
-    static_assert(W_T % G == 0, "groups must tile the workers");
+    constexpr int NG = (W_T + G - 1) / G;  // the last group may be short
 
     const ptr_table_t pg = row + col_grad(a.wtot, a.wfirst);
     const ptr_table_t pu = row + col_local(a.wtot, a.wfirst);
@@ -361,16 +360,19 @@ __device__ __forceinline__ void apply_fixed(ptr_table_t row, const KernelArgs &a
     auto issue_loads = [&](int grp, int buf) {
 #pragma unroll
         for (int j = 0; j < G; ++j)
-            g[buf][j] = load<ODSGD_NT_GRAD, T>(pg[grp * G + j], boff);
+            if (grp * G + j < W_T)
+                g[buf][j] = load<ODSGD_NT_GRAD, T>(pg[grp * G + j], boff);
         if constexpr (need_u_old) {
 #pragma unroll
             for (int j = 0; j < G; ++j)
-                u_old[buf][j] = load<ODSGD_NT_INPLACE_LD, T>(pu[grp * G + j], boff);
+                if (grp * G + j < W_T)
+                    u_old[buf][j] = load<ODSGD_NT_INPLACE_LD, T>(pu[grp * G + j], boff);
         }
         if constexpr (need_state) {
 #pragma unroll
             for (int j = 0; j < G; ++j)
-                st_old[buf][j] = load<ODSGD_NT_INPLACE_LD, T>(ps[grp * G + j], boff);
+                if (grp * G + j < W_T)
+                    st_old[buf][j] = load<ODSGD_NT_INPLACE_LD, T>(ps[grp * G + j], boff);
         }
     };
 
@@ -384,6 +386,8 @@ __device__ __forceinline__ void apply_fixed(ptr_table_t row, const KernelArgs &a
             issue_loads(grp + 1, buf ^ 1);
 #pragma unroll
         for (int j = 0; j < G; ++j) {
+            if (grp * G + j >= W_T)
+                break;
             const T gm = g[buf][j];
             if constexpr (MODE != MODE_LOCAL)
                 s = (grp == 0 && j == 0) ? gm : s + gm;
@@ -822,9 +826,19 @@ KernelFn pick_by_workers(int wcount)
     switch (wcount) {
     case 1: return odsgd_kernel<1, MODE, RULE>;
     case 2: return odsgd_kernel<2, MODE, RULE>;
+    case 3: return odsgd_kernel<3, MODE, RULE>;
     case 4: return odsgd_kernel<4, MODE, RULE>;
+    case 5: return odsgd_kernel<5, MODE, RULE>;
+    case 6: return odsgd_kernel<6, MODE, RULE>;
+    case 7: return odsgd_kernel<7, MODE, RULE>;
     case 8: return odsgd_kernel<8, MODE, RULE>;
+    case 9: return odsgd_kernel<9, MODE, RULE>;
+    case 10: return odsgd_kernel<10, MODE, RULE>;
+    case 11: return odsgd_kernel<11, MODE, RULE>;
     case 12: return odsgd_kernel<12, MODE, RULE>;
+    case 13: return odsgd_kernel<13, MODE, RULE>;
+    case 14: return odsgd_kernel<14, MODE, RULE>;
+    case 15: return odsgd_kernel<15, MODE, RULE>;
     case 16: return odsgd_kernel<16, MODE, RULE>;
     default: return odsgd_kernel<0, MODE, RULE>;
     }

@@ -70,7 +70,7 @@ def test_hand_expanded_literals_on_gpu(golden_dcasgd):
 
 
 @pytest.mark.parametrize("rule", ["c", "a", "m"])
-@pytest.mark.parametrize("W", [1, 3, 4, 8, 12, 16])
+@pytest.mark.parametrize("W", [1, 3, 4, 6, 8, 9, 12, 13, 16, 18])
 def test_rules_ragged_sizes_schedule_and_split_calls(rule, W):
     say("rule=%s W=%d" % (rule, W))
     st, arenas, gen = custom_state(RAGGED, W, seed=300 + W)

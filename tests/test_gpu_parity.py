@@ -127,7 +127,7 @@ def test_probe_copy():
 # ---------------------------------------------------------------------------
 # worker counts (templated and generic kernels), ragged sizes, guard bands
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("W", [1, 2, 3, 4, 5, 7, 8, 12, 16, 17, 64])
+@pytest.mark.parametrize("W", [1, 2, 3, 4, 5, 6, 7, 8, 9, 11, 12, 13, 15, 16, 17, 64])
 def test_worker_counts_ragged_sizes_all_entry_points(W):
     say("W=%d sizes=%s" % (W, RAGGED))
     st, arenas, gen = custom_state(RAGGED, W, seed=100 + W)
@@ -174,7 +174,7 @@ BLOCKY = [16384 * 3 + 77, 5, 16384, 16383, 20000, 16384 * 2, 1, 70000]
 
 
 @pytest.mark.parametrize("block_phase", [0, 512, 1040, 65536 - 16, 32768 + 256])
-@pytest.mark.parametrize("W", [2, 8, 16, 5])
+@pytest.mark.parametrize("W", [2, 8, 16, 5, 13, 20])
 def test_two_half_tiles_all_entry_points(W, block_phase):
     """Every array of a tensor at the same offset from a 64 KiB boundary: the blocks inside
     take two-half tiles, the pieces before and after them contiguous ones; the oracle knows
