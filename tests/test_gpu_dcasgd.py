@@ -136,6 +136,43 @@ def test_workloads_with_rules(name, rule, iters):
     eng.close()
 
 
+@pytest.mark.parametrize("rule", ["c", "a", "m"])
+@pytest.mark.parametrize("W,state_phase", [(4, 512), (16, 512), (13, 512), (8, 1536)])
+def test_rules_on_two_half_tiles(rule, W, state_phase):
+    """Tensors longer than a 64 KiB block, every array 512 bytes past a block boundary: the rules run
+    on two-half tiles.  With the per-worker state at a different offset (1536) the registration
+    moves those tensors back to contiguous tiles; the results are the same either way."""
+    sizes = [16384 * 2 + 300, 16384, 700]
+    say("rule=%s W=%d state_phase=%d" % (rule, W, state_phase))
+    st, arenas, gen = custom_state(sizes, W, seed=420 + W, block_phase=512)
+    for m in range(W):
+        for k, t in enumerate(st["u"][m]):
+            t.copy_(st["w"][k] + 1e-3 * torch.randn(t.shape, generator=gen, device=DEV))
+    ms_arenas = [Arena(sizes, block_phase=state_phase) for _ in range(W)]
+    ms = [a.views for a in ms_arenas]
+    for r in ms:
+        for t in r:
+            t.zero_()
+    hs = host_state(st)
+    ms_h = [to_host(r) for r in ms]
+    eng = make_engine(st, warmup_steps=1)
+    hy = (0.05, 0.02, 0.9, 1e-3, 0.0)
+    oh = oracle_hyper(hy)
+    orule = install_rule(eng, rule, ms, ms_h)
+    for it in range(4):
+        eng.step(hy)
+        oracle.step(it, 1, hs["w"], hs["v"], hs["g"], hs["u"], rule=orule, **oh)
+        assert compare(st, hs, label="fused it %d" % it)[0] == 0 and compare_ms(ms, ms_h) == 0
+        regen_grads(st, gen, gstd=1e-2)
+        refresh_host_grads(st, hs)
+    eng.local_update(-1, hy)
+    eng.global_update(hy)
+    oracle.step(4, 1, hs["w"], hs["v"], hs["g"], hs["u"], rule=orule, **oh)
+    assert compare(st, hs, label="local(all)+global")[0] == 0 and compare_ms(ms, ms_h) == 0
+    assert arenas_intact(arenas) and all(a.intact() for a in ms_arenas)
+    eng.close()
+
+
 @pytest.mark.parametrize("rule", ["a", "m"])
 def test_state_that_is_only_4_byte_aligned_moves_the_tensor_to_the_32_bit_path(rule):
     W, sizes = 3, [1000, 7, 4096]
