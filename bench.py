@@ -45,6 +45,14 @@ def algorithmic_bytes(n_params, W):
     return 8 * (W + 2) * n_params
 
 
+def device_code_sha256():
+    """Hash of the device part of the kernel source file (everything above its "host side"
+    marker): what a counter summary under profiles/ is valid for."""
+    text = open(KERNEL_SOURCE, "rb").read()
+    cut = text.find(b"\n// host side\n")
+    return hashlib.sha256(text if cut < 0 else text[:cut]).hexdigest()
+
+
 def measured_traffic(workload):
     """HBM bytes per launch from the rocprofv3 counter summary under profiles/, if that summary
     was made from the kernel source this run times; otherwise null with the reason."""
@@ -54,14 +62,14 @@ def measured_traffic(workload):
         return None, "no counter summary %s" % rel
     text = open(path).read()
     m = re.search(r"measured HBM traffic per launch: ([0-9.eE+]+) bytes", text)
-    sha = re.search(r"kernel source sha256: ([0-9a-f]{64})", text)
+    sha = re.search(r"device code sha256: ([0-9a-f]{64})", text)
     if not m or not sha:
         return None, "%s holds no traffic figure" % rel
-    now = hashlib.sha256(open(KERNEL_SOURCE, "rb").read()).hexdigest()
+    now = device_code_sha256()
     if sha.group(1) != now:
-        return None, "%s was measured on an older kernel source (sha256 %s...)" % (rel, sha.group(1)[:12])
+        return None, "%s was measured on other device code (sha256 %s...)" % (rel, sha.group(1)[:12])
     return float(m.group(1)), "%s: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE, scaled by the same counters on " \
-                              "the 1 GiB copy probe; same kernel source (sha256 %s...)" % (rel, now[:12])
+                              "the 1 GiB copy probe; same device code (sha256 %s...)" % (rel, now[:12])
 
 
 def launch_stats(ms, nbytes):

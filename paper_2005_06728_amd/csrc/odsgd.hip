@@ -724,6 +724,10 @@ int make_plan(Plan &plan, const Registration &reg, const Tuning &tuning)
 
     int64_t c = 0, r = 0;
     auto emit = [&](int64_t row, bool vec, int64_t off, int64_t cnt, uint32_t second) {
+        if (c >= max_chunks) {  // never taken (see count_tables); keeps a counting mistake from becoming an overrun
+            ++c;
+            return;
+        }
         uint32_t *dsc = ct + c * 4;
         dsc[0] = (uint32_t)row | (vec ? kVecFlag : 0u);
         dsc[1] = (uint32_t)cnt;
