@@ -874,6 +874,8 @@ KernelFn pick_kernel(int mode, int rule, int wcount)
 // residency: how many one-wavefront workgroups a CU should hold, and the dynamic
 // LDS request that makes it so
 // ---------------------------------------------------------------------------
+constexpr int kMaxUnrolledWorkers = 16;  // odsgd_kernel<W_T, ...> exists for W_T = 1..16; more workers take W_T = 0
+
 // distinct arrays a launch streams through (an array updated in place counts once)
 int arrays_per_tile(int mode, int rule, int wcount)
 {
@@ -899,6 +901,11 @@ int wanted_waves(int mode, int rule, int wcount, int override_waves)
         return 0;
     int waves = override_waves;
     if (waves == 0) {
+        // beyond the unrolled worker counts the kernel walks the workers one after the other,
+        // one memory latency each: that loop needs every wavefront it can get (W = 32 on the
+        // ResNet-50-shaped set: 0.82 of peak unlimited, 0.23 at two wavefronts per CU)
+        if (wcount > kMaxUnrolledWorkers)
+            return 0;
         const int arrays = arrays_per_tile(mode, rule, wcount);
         waves = (ODSGD_INFLIGHT_MEMOPS_PER_CU + arrays / 2) / arrays;  // nearest integer
         // the adaptive rule spends a correctly rounded sqrt and divide per element and
