@@ -525,3 +525,46 @@ def test_two_handles_on_two_streams_are_independent():
             oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], **oracle_hyper(hy))
         assert compare(st, hs)[0] == 0
         eng.close()
+
+
+# ---------------------------------------------------------------------------
+# the whole loop of Alg. 2 closed on the GPU: gradients computed from the weights
+# each worker was handed, warm-up, switching and training stages in one run
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("wp", [0, 1, 3])
+def test_closed_training_loop_on_gpu_follows_the_oracle(wp):
+    """Worker m minimises 0.5*a*(x - c_m)^2 per coordinate: its gradient is a*(x_m - c_m) at the
+    weights x_m it was handed -- the exact global weights during warm-up, its compensated local
+    weights afterwards.  The same loop runs on the host with the oracle; the gradient is two
+    separately rounded binary32 operations on both sides, so every iteration must agree bit for bit."""
+    W, sizes, steps = 4, [1000, 3, 16384 * 2 + 5], 12
+    a = 0.5
+    st, arenas, gen = custom_state(sizes, W, seed=800 + wp, wstd=1.0, block_phase=0)
+    centres = [[torch.randn(n, device=DEV, generator=gen) for n in sizes] for _ in range(W)]
+    for k, t in enumerate(st["v"]):
+        t.zero_()
+    for m in range(W):
+        for k, t in enumerate(st["u"][m]):
+            t.copy_(st["w"][k])            # workers pull w_0 before the first iteration
+    hs = host_state(st)
+    hc = [to_host(r) for r in centres]
+    eng = make_engine(st, warmup_steps=wp)
+    hy = (0.25, 0.375, 0.9, 1e-3, 0.0)
+    oh = oracle_hyper(hy)
+    for it in range(steps):
+        for m in range(W):
+            for k in range(len(sizes)):
+                torch.mul(torch.sub(st["u"][m][k], centres[m][k]), a, out=st["g"][m][k])
+                hs["g"][m][k][...] = (hs["u"][m][k] - hc[m][k]) * np.float32(a)
+        eng.step(hy)
+        oracle.step(it, wp, hs["w"], hs["v"], hs["g"], hs["u"], **oh)
+        assert compare(st, hs, label="closed loop wp=%d it %d" % (wp, it))[0] == 0
+        handed_equals_global = all(torch.equal(st["u"][m][k], st["w"][k]) for m in range(W) for k in range(len(sizes)))
+        assert handed_equals_global == (it < wp), "iteration %d" % it
+    # and the loop does what training is for: the weights move towards the mean of the workers' centres
+    mean_c = [sum(centres[m][k] for m in range(W)) / W for k in range(len(sizes))]
+    dist = sum(float(torch.sum((w_ - c) ** 2)) for w_, c in zip(st["w"], mean_c))
+    start = sum(float(torch.sum(c ** 2)) for c in mean_c) + sum(sizes)   # E|w_0 - c|^2 with w_0 ~ N(0, 1)
+    assert dist < 0.5 * start
+    assert arenas_intact(arenas)
+    eng.close()
