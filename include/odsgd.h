@@ -29,11 +29,13 @@
  * "host" are read during the call only.
  *
  * Tuning.  Launch shape is chosen per call from the worker count and entry
- * point; three environment variables, read by odsgd_init, override it for
+ * point; a few environment variables, read by odsgd_init, override it for
  * experiments and never change results: ODSGD_WAVES_PER_CU
  * (resident wavefronts per compute unit; 0 = automatic, negative = uncapped),
  * ODSGD_BLOCKS_PER_CU (> 0: persistent grid), ODSGD_PAIR_BIT (address bit that
- * separates the two halves of a tile, default 15; 0 = contiguous tiles only).
+ * separates the two halves of a tile, default 15; 0 = contiguous tiles only),
+ * ODSGD_LLC_BYTES (size of the last-level cache, default 256 MiB: weights plus
+ * momentum beyond it are loaded non-temporally by odsgd_global_update).
  *
  * Layout advice.  The update runs fastest when, for each tensor, all arrays
  * (w, mom, every grads[m] and local_w[m], state) start at the same offset from

@@ -48,7 +48,7 @@ def resource_usage(defines=()):
     cmd = [hipcc, *flags, *["-D" + d for d in defines], "--cuda-device-only", "-c", SRC, "-o", os.devnull,
            "-Rpass-analysis=kernel-resource-usage"]
     text = subprocess.run(cmd, check=True, capture_output=True, text=True).stderr
-    modes = {0: "od", 1: "ssgd", 2: "global", 3: "local", 4: "copy probe"}
+    modes = {0: "od", 1: "ssgd", 2: "global", 3: "local", 4: "copy probe", 5: "global, streamed state"}
     rules = {0: "sgd", 1: "dcasgd_c", 2: "dcasgd_a", 3: "momentum"}
     rows = []
     for block in re.split(r"remark: Function Name: ", text)[1:]:

@@ -568,3 +568,39 @@ def test_closed_training_loop_on_gpu_follows_the_oracle(wp):
     assert dist < 0.5 * start
     assert arenas_intact(arenas)
     eng.close()
+
+
+@pytest.mark.parametrize("W", [3, 16, 20])
+def test_global_update_that_streams_its_state(W):
+    """Weights plus momentum larger than the last-level cache make odsgd_global_update load them
+    non-temporally (another kernel variant); forced here by declaring the cache empty."""
+    old = os.environ.get("ODSGD_LLC_BYTES")
+    os.environ["ODSGD_LLC_BYTES"] = "0"
+    try:
+        st, arenas, gen = custom_state(BLOCKY, W, seed=850 + W, block_phase=0)
+        hs = host_state(st)
+        eng = make_engine(st)
+    finally:
+        if old is None:
+            os.environ.pop("ODSGD_LLC_BYTES")
+        else:
+            os.environ["ODSGD_LLC_BYTES"] = old
+    hy = (0.05, 0.02, 0.9, 1e-3, 0.0)
+    oh = oracle_hyper(hy)
+    for it in range(3):
+        eng.local_update(-1, hy)
+        eng.global_update(hy)
+        oracle.od_step(hs["w"], hs["v"], hs["g"], hs["u"], **oh)
+        assert compare(st, hs, label="it %d" % it)[0] == 0
+        regen_grads(st, gen)
+        refresh_host_grads(st, hs)
+    # global update alone: local weights untouched
+    before_u = [to_host(r) for r in st["u"]]
+    eng.global_update(hy)
+    oracle.global_update(hs["w"], hs["v"], hs["g"], oh["lr"], oh["momentum"], oh["weight_decay"], oh["grad_scale"])
+    assert compare(st, hs, what=("w", "v"))[0] == 0
+    for m in range(W):
+        for a, b in zip(to_host(st["u"][m]), before_u[m]):
+            assert same_bits(a, b)
+    assert arenas_intact(arenas)
+    eng.close()
