@@ -337,7 +337,7 @@ __device__ __forceinline__ void local_one(T w0, T gm, T r, T u_old, T st_old, ui
 // few scalar spills the stateful rules keep at W >= 12, but was measured 1 %
 // slower, so the scheduler is left free.)
 // The gradient sum is accumulated as the groups go by, in ascending worker
-// order, so the result is the same left-to-right sum as before.
+// order: the same left-to-right sum a single loop over the workers gives.
 // ---------------------------------------------------------------------------
 template <int W_T, int MODE, int RULE>
 constexpr int group_size()
