@@ -45,10 +45,13 @@ def test_hand_expanded_sequence_on_gpu(golden_w2):
 # ---------------------------------------------------------------------------
 # the five parameter sets, fused step, all outputs compared after every iteration
 # ---------------------------------------------------------------------------
-def run_workload(name, iterations, warmup=0, layout="separate", every_output=None):
+def run_workload(name, iterations, warmup=0, layout="separate", every_output=None, threads=1):
     """every_output(it) -> compare w, momentum and all local weights after iteration `it`
     (default: always); otherwise only w and momentum, which carry the accumulated state --
-    the local weights are rewritten from scratch by every iteration."""
+    the local weights are rewritten from scratch by every iteration.  threads > 1 runs the
+    oracle's one-step-delay iteration with its element range split over that many host
+    threads (the same C routine per piece; the split is pinned against the unsplit call in
+    the host-only tests), which keeps the full-length runs of the large sets short."""
     w = wl.WORKLOADS[name]
     say("workload %s: K=%d N=%d W=%d iterations=%d warmup=%d" %
         (name, len(w.tensors), wl.total_params(w), w.num_workers, iterations, warmup))
@@ -62,7 +65,10 @@ def run_workload(name, iterations, warmup=0, layout="separate", every_output=Non
         wl.fill_all_grads_(st, w, it)
         refresh_host_grads(st, hs)
         eng.step(hy)
-        oracle.step(it, warmup, hs["w"], hs["v"], hs["g"], hs["u"], **oh)
+        if threads > 1 and it >= warmup:
+            oracle.od_step_threads(hs["w"], hs["v"], hs["g"], hs["u"], threads=threads, **oh)
+        else:
+            oracle.step(it, warmup, hs["w"], hs["v"], hs["g"], hs["u"], **oh)
         what = ("w", "v", "u") if every_output is None or every_output(it) else ("w", "v")
         bad, worst = compare(st, hs, what=what, label="%s it %d" % (name, it))
         total_bad += bad
@@ -70,6 +76,9 @@ def run_workload(name, iterations, warmup=0, layout="separate", every_output=Non
     say("  %s: %d elements differ bitwise from the oracle" % (name, total_bad))
     eng.close()
     return total_bad
+
+
+HOST_THREADS = min(16, os.cpu_count() or 1)
 
 
 def ends_only(iterations):
@@ -87,17 +96,17 @@ def test_resnet20_full_run_heavy_tailed_gradients():
 
 def test_resnet50_full_size_full_run():
     n = wl.WORKLOADS["resnet50"].iterations
-    assert n == 50 and run_workload("resnet50", n, every_output=ends_only(n)) == 0
+    assert n == 50 and run_workload("resnet50", n, every_output=ends_only(n), threads=HOST_THREADS) == 0
 
 
 def test_alexnet_full_size_full_run():
     n = wl.WORKLOADS["alexnet"].iterations
-    assert n == 20 and run_workload("alexnet", n, every_output=ends_only(n)) == 0
+    assert n == 20 and run_workload("alexnet", n, every_output=ends_only(n), threads=HOST_THREADS) == 0
 
 
 def test_vgg16_full_size_full_run_with_exact_zero_gradients():
     n = wl.WORKLOADS["vgg16"].iterations
-    assert n == 10 and run_workload("vgg16", n, every_output=ends_only(n)) == 0
+    assert n == 10 and run_workload("vgg16", n, every_output=ends_only(n), threads=HOST_THREADS) == 0
 
 
 def test_resnet20_with_warmup_schedule():
